@@ -1,0 +1,137 @@
+"""Seeded synthetic convolution workloads.
+
+Layer shapes and value distributions that stand in for the CNN layers the paper
+evaluates (Section 5.1, "Set up": forward convolutions of ResNet-50 at mini-batch 28,
+channel widths that are multiples of 16).  The paper runs on trained networks and real
+images; convolution time does not depend on the values, so seeded random tensors of the
+same shapes are used instead.
+
+This module holds no convolution arithmetic: only shapes, seeds and random draws.  It is
+the one module that both the CPU oracle's tests and the GPU path's tests import, so that
+both sides see the very same input bits.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, asdict
+import math
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class ConvShape:
+    """Problem sizes of one forward convolution (the loop bounds of the paper's Fig. 4)."""
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    R: int
+    S: int
+    stride: int = 1
+    pad: int = 0
+    name: str = ""
+
+    @property
+    def P(self) -> int:
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def Q(self) -> int:
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+    @property
+    def flops(self) -> int:
+        """2*N*K*P*Q*C*R*S with the real channel count (the headline convention)."""
+        return 2 * self.N * self.K * self.P * self.Q * self.C * self.R * self.S
+
+    @property
+    def flops_issued(self) -> int:
+        """Same with C rounded up to the 16-wide channel block (work the matrix cores issue)."""
+        c16 = -(-self.C // 16) * 16
+        return 2 * self.N * self.K * self.P * self.Q * c16 * self.R * self.S
+
+    def algorithmic_bytes(self, elem_size: int = 4) -> int:
+        """Each of input, filter and output touched once (output is always fp32)."""
+        c16 = -(-self.C // 16) * 16
+        return (self.N * c16 * self.H * self.W * elem_size
+                + self.K * c16 * self.R * self.S * elem_size
+                + self.N * self.K * self.P * self.Q * 4)
+
+    def as_dict(self) -> dict:
+        d = asdict(self)
+        d["P"], d["Q"] = self.P, self.Q
+        return d
+
+
+# --- the five benchmark configurations -------------------------------------------------
+MINIBATCH = 28  # Section 5.1: mini-batch 28, one image per core
+
+CFG1 = ConvShape(1, 64, 14, 14, 64, 3, 3, 1, 1, "cfg1_3x3_64_14")
+CFG2 = ConvShape(MINIBATCH, 64, 56, 56, 64, 3, 3, 1, 1, "3x3_64_56")
+CFG3A = ConvShape(MINIBATCH, 256, 56, 56, 64, 1, 1, 1, 0, "1x1_256to64_56")
+CFG3B = ConvShape(MINIBATCH, 512, 28, 28, 1024, 1, 1, 2, 0, "1x1s2_512to1024_28")
+
+
+def resnet50_layers(N: int = MINIBATCH) -> list[ConvShape]:
+    """ResNet-50-shaped layer sweep: four 3x3 layers, eight 1x1 layers, and the 7x7 stem."""
+    layers = []
+    for c, hw in ((64, 56), (128, 28), (256, 14), (512, 7)):
+        layers.append(ConvShape(N, c, hw, hw, c, 3, 3, 1, 1, f"3x3_{c}_{hw}"))
+    for (a, b), hw in (((64, 256), 56), ((128, 512), 28), ((256, 1024), 14), ((512, 2048), 7)):
+        layers.append(ConvShape(N, a, hw, hw, b, 1, 1, 1, 0, f"1x1_{a}to{b}_{hw}"))
+        layers.append(ConvShape(N, b, hw, hw, a, 1, 1, 1, 0, f"1x1_{b}to{a}_{hw}"))
+    layers.append(ConvShape(N, 3, 224, 224, 64, 7, 7, 2, 3, "stem_7x7s2_3to64_224"))
+    return layers
+
+
+def sweep_seed(layer_index: int) -> int:
+    return 100 + layer_index
+
+
+# --- value distributions ---------------------------------------------------------------
+def uniform_pm1(shape: ConvShape, seed: int) -> tuple[np.ndarray, np.ndarray]:
+    """Input and filter iid uniform on [-1, 1) (the small single-layer configuration)."""
+    rng = np.random.default_rng(seed)
+    x = rng.uniform(-1.0, 1.0, size=(shape.N, shape.C, shape.H, shape.W)).astype(np.float32)
+    w = rng.uniform(-1.0, 1.0, size=(shape.K, shape.C, shape.R, shape.S)).astype(np.float32)
+    return x, w
+
+
+def relu_like(shape: ConvShape, seed: int) -> tuple[np.ndarray, np.ndarray]:
+    """Input uniform on [0, 1) (post-ReLU-like); filter normal with std sqrt(2/(C*R*S))."""
+    rng = np.random.default_rng(seed)
+    x = rng.random(size=(shape.N, shape.C, shape.H, shape.W), dtype=np.float32)
+    sigma = math.sqrt(2.0 / (shape.C * shape.R * shape.S))
+    w = (rng.standard_normal(size=(shape.K, shape.C, shape.R, shape.S), dtype=np.float32)
+         * np.float32(sigma))
+    return x, w
+
+
+def small_integers(shape: ConvShape, seed: int, lo: int = -2, hi: int = 2) -> tuple[np.ndarray, np.ndarray]:
+    """Integer-valued tensors in [lo, hi]: every partial sum is exact in fp32 and in bf16
+    products, so a correct implementation reproduces the exact result bit for bit."""
+    rng = np.random.default_rng(seed)
+    x = rng.integers(lo, hi + 1, size=(shape.N, shape.C, shape.H, shape.W)).astype(np.float32)
+    w = rng.integers(lo, hi + 1, size=(shape.K, shape.C, shape.R, shape.S)).astype(np.float32)
+    return x, w
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bfloat16 (ties to even); returned widened to fp32.
+
+    Input preparation for the bf16 configuration: both the oracle and the GPU path consume
+    these already-rounded values."""
+    bits = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    is_nan = (bits & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+    lsb = (bits >> np.uint32(16)) & np.uint32(1)
+    rounded = (bits + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    out = np.where(is_nan, bits | np.uint32(0x00400000), rounded).astype(np.uint32)
+    out = out & np.uint32(0xFFFF0000)
+    return out.view(np.float32).reshape(a.shape)
+
+
+def bf16_bits(a_rounded: np.ndarray) -> np.ndarray:
+    """The 16-bit patterns of values that are already exactly representable in bfloat16."""
+    bits = np.ascontiguousarray(a_rounded, dtype=np.float32).view(np.uint32)
+    return (bits >> np.uint32(16)).astype(np.uint16).reshape(a_rounded.shape)

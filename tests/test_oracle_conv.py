@@ -1,0 +1,233 @@
+"""Pins for the CPU oracle: the convolution definition checked against closed forms,
+special cases that reduce to library routines, and brute force on tiny shapes.  Each pin is
+chosen so that a plausible slip in the oracle (dropped term, flipped filter, swapped r/s or
+h/w, wrong pad sign, wrong stride placement) fails at least one of them."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from paper_2002_02145_amd.workloads import ConvShape, uniform_pm1, relu_like, small_integers
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_hand_worked_golden(oracle_lib):
+    x = np.arange(1, 10, dtype=np.float32).reshape(1, 1, 3, 3)
+    w = np.array([[1, 0], [0, -1]], dtype=np.float32).reshape(1, 1, 2, 2)
+    seen = 0
+    for line in open(os.path.join(GOLDEN, "conv_hand_worked.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        tok = line.split()
+        stride, pad, P, Q = map(int, tok[1:5])
+        want = np.array(list(map(float, tok[5:]))).reshape(1, 1, P, Q)
+        sh = ConvShape(1, 1, 3, 3, 1, 2, 2, stride, pad)
+        assert (sh.P, sh.Q) == (P, Q)
+        assert oracle_lib.out_dims(sh) == (P, Q)
+        out, _ = oracle_lib.conv2d_fwd(sh, x, w)
+        np.testing.assert_array_equal(out, want)
+        seen += 1
+    assert seen == 3
+
+
+def test_output_dims_of_benchmark_shapes(oracle_lib):
+    # 3x3 pad 1 keeps the size; 1x1 stride 2 halves 28 -> 14; 7x7 stride 2 pad 3 maps 224 -> 112
+    assert oracle_lib.out_dims(ConvShape(1, 16, 56, 56, 16, 3, 3, 1, 1)) == (56, 56)
+    assert oracle_lib.out_dims(ConvShape(1, 16, 28, 28, 16, 1, 1, 2, 0)) == (14, 14)
+    assert oracle_lib.out_dims(ConvShape(1, 3, 224, 224, 16, 7, 7, 2, 3)) == (112, 112)
+    # floor division: H + 2 pad - R not divisible by stride
+    assert oracle_lib.out_dims(ConvShape(1, 1, 8, 9, 1, 3, 3, 2, 0)) == (3, 4)
+    with pytest.raises(ValueError):
+        oracle_lib.out_dims(ConvShape(1, 1, 2, 2, 1, 3, 3, 1, 0))
+
+
+def test_1x1_stride1_is_matmul(oracle_lib):
+    sh = ConvShape(3, 37, 5, 6, 32, 1, 1, 1, 0)
+    x, w = uniform_pm1(sh, 11)
+    out, mag = oracle_lib.conv2d_fwd(sh, x, w)
+    W = w.reshape(sh.K, sh.C).astype(np.float64)
+    X = x.astype(np.float64)
+    want = np.einsum("kc,nchw->nkhw", W, X)
+    np.testing.assert_allclose(out, want, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(mag, np.einsum("kc,nchw->nkhw", np.abs(W), np.abs(X)), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("stride,pad,R,S", [(1, 1, 3, 3), (2, 3, 7, 7), (2, 0, 1, 1), (1, 0, 2, 3), (3, 2, 3, 2)])
+def test_delta_input_reads_out_the_filter(oracle_lib, stride, pad, R, S):
+    sh = ConvShape(2, 3, 9, 8, 16, R, S, stride, pad)
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal((sh.K, sh.C, R, S)).astype(np.float32)
+    n0, c0, h0, w0 = 1, 2, 4, 3
+    x = np.zeros((sh.N, sh.C, sh.H, sh.W), np.float32)
+    x[n0, c0, h0, w0] = 1.0
+    out, _ = oracle_lib.conv2d_fwd(sh, x, w)
+    want = np.zeros_like(out)
+    for p in range(sh.P):
+        for q in range(sh.Q):
+            r, s = h0 + pad - p * stride, w0 + pad - q * stride
+            if 0 <= r < R and 0 <= s < S:
+                want[n0, :, p, q] = w[:, c0, r, s]
+    np.testing.assert_array_equal(out, want)
+    assert np.count_nonzero(out[0]) == 0
+
+
+def test_identity_filter_reproduces_input(oracle_lib):
+    sh = ConvShape(2, 16, 7, 9, 16, 3, 5, 1, 0)
+    x, _ = uniform_pm1(sh, 3)
+    # centre tap identity needs pad (R-1)/2 and (S-1)/2; the oracle has one pad, so use a square filter
+    sh = ConvShape(2, 16, 7, 9, 16, 5, 5, 1, 2)
+    w = np.zeros((16, 16, 5, 5), np.float32)
+    for k in range(16):
+        w[k, k, 2, 2] = 1.0
+    out, mag = oracle_lib.conv2d_fwd(sh, x, w)
+    np.testing.assert_array_equal(out, x.astype(np.float64))
+    np.testing.assert_array_equal(mag, np.abs(x).astype(np.float64))
+
+
+def test_off_centre_tap_shifts_the_image(oracle_lib):
+    # a single 1 at tap (r0, s0) makes out[p][q] = x(p + r0 - pad, q + s0 - pad): direction of
+    # the shift distinguishes correlation from a flipped filter and r from s
+    sh = ConvShape(1, 1, 6, 7, 16, 3, 3, 1, 1)
+    x, _ = uniform_pm1(sh, 8)
+    w = np.zeros((16, 1, 3, 3), np.float32)
+    w[:, 0, 0, 2] = 1.0     # r0 = 0 (row above), s0 = 2 (column to the right)
+    out, _ = oracle_lib.conv2d_fwd(sh, x, w)
+    want = np.zeros((6, 7))
+    want[1:, :-1] = x[0, 0, :-1, 1:]
+    np.testing.assert_array_equal(out[0, 5], want)
+
+
+def test_linearity_in_input_and_filter(oracle_lib):
+    sh = ConvShape(2, 5, 6, 7, 16, 3, 3, 2, 1)
+    x1, w1 = uniform_pm1(sh, 21)
+    x2, w2 = uniform_pm1(sh, 22)
+    a = np.float32(0.5)
+    # quantise to 6 fractional bits so that a*x1 + x2 is exactly representable in fp32
+    q = lambda t: (np.round(t * 64) / 64).astype(np.float32)
+    x1q, x2q, w1q, w2q = q(x1), q(x2), q(w1), q(w2)
+    o1, _ = oracle_lib.conv2d_fwd(sh, x1q, w1q)
+    o2, _ = oracle_lib.conv2d_fwd(sh, x2q, w1q)
+    o12, _ = oracle_lib.conv2d_fwd(sh, a * x1q + x2q, w1q)
+    np.testing.assert_allclose(o12, 0.5 * o1 + o2, rtol=0, atol=1e-12)
+    o3, _ = oracle_lib.conv2d_fwd(sh, x1q, w2q)
+    o13, _ = oracle_lib.conv2d_fwd(sh, x1q, a * w1q + w2q)
+    np.testing.assert_allclose(o13, 0.5 * o1 + o3, rtol=0, atol=1e-12)
+
+
+def _toeplitz(sh, w):
+    """Dense matrix T with out.flat = T @ x.flat for one image (input-indexed construction)."""
+    T = np.zeros((sh.K * sh.P * sh.Q, sh.C * sh.H * sh.W))
+    for k, p, q, c, h, ww in itertools.product(range(sh.K), range(sh.P), range(sh.Q),
+                                               range(sh.C), range(sh.H), range(sh.W)):
+        r = h - (p * sh.stride - sh.pad)
+        s = ww - (q * sh.stride - sh.pad)
+        if 0 <= r < sh.R and 0 <= s < sh.S:
+            T[(k * sh.P + p) * sh.Q + q, (c * sh.H + h) * sh.W + ww] = w[k, c, r, s]
+    return T
+
+
+@pytest.mark.parametrize("R,stride,pad", [(1, 1, 0), (1, 2, 0), (3, 1, 1), (3, 2, 1), (3, 1, 0),
+                                          (7, 2, 3), (3, 2, 3), (2, 1, 1)])
+def test_toeplitz_brute_force(oracle_lib, R, stride, pad):
+    H, W = (6, 5) if R < 7 else (8, 7)
+    sh = ConvShape(2, 3, H, W, 2, R, R, stride, pad)
+    rng = np.random.default_rng(R * 100 + stride * 10 + pad)
+    x = rng.standard_normal((sh.N, sh.C, H, W)).astype(np.float32)
+    w = rng.standard_normal((sh.K, sh.C, R, R)).astype(np.float32)
+    out, mag = oracle_lib.conv2d_fwd(sh, x, w)
+    T = _toeplitz(sh, w.astype(np.float64))
+    for n in range(sh.N):
+        np.testing.assert_allclose(out[n].ravel(), T @ x[n].astype(np.float64).ravel(), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(mag[n].ravel(), np.abs(T) @ np.abs(x[n]).astype(np.float64).ravel(),
+                                   rtol=0, atol=1e-12)
+
+
+def test_non_square_filter_toeplitz(oracle_lib):
+    sh = ConvShape(1, 2, 7, 6, 3, 2, 3, 2, 1)
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((1, 2, 7, 6)).astype(np.float32)
+    w = rng.standard_normal((3, 2, 2, 3)).astype(np.float32)
+    out, _ = oracle_lib.conv2d_fwd(sh, x, w)
+    np.testing.assert_allclose(out[0].ravel(), _toeplitz(sh, w.astype(np.float64)) @ x[0].astype(np.float64).ravel(),
+                               rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("R,stride,pad,H,W", [(3, 1, 1, 6, 7), (7, 2, 3, 12, 11), (3, 2, 1, 8, 8), (1, 2, 0, 5, 6)])
+def test_all_ones_counts_in_bounds_taps(oracle_lib, R, stride, pad, H, W):
+    C = 5
+    sh = ConvShape(1, C, H, W, 16, R, R, stride, pad)
+    x = np.ones((1, C, H, W), np.float32)
+    w = np.ones((16, C, R, R), np.float32)
+    out, mag = oracle_lib.conv2d_fwd(sh, x, w)
+    rows = np.array([sum(0 <= p * stride + r - pad < H for r in range(R)) for p in range(sh.P)])
+    cols = np.array([sum(0 <= q * stride + s - pad < W for s in range(R)) for q in range(sh.Q)])
+    want = C * np.outer(rows, cols).astype(np.float64)
+    for k in (0, 7, 15):
+        np.testing.assert_array_equal(out[0, k], want)
+    np.testing.assert_array_equal(mag, out)
+
+
+def test_blocked_batch_reduce_formulation_agrees(oracle_lib):
+    """The paper's Fig. 4 computes the same thing on blocked, physically padded arrays as a
+    batch of small GEMMs reduced over (ifm_tile, kj, ki).  Written here with numpy matmuls on
+    the blocked layouts; must equal the definition after the layout transforms."""
+    from oracle import layout
+    for sh, seed in ((ConvShape(2, 32, 6, 7, 32, 3, 3, 1, 1), 1), (ConvShape(1, 20, 9, 9, 16, 3, 3, 2, 1), 2),
+                     (ConvShape(2, 48, 5, 5, 32, 1, 1, 1, 0), 3)):
+        x, w = uniform_pm1(sh, seed)
+        out, _ = oracle_lib.conv2d_fwd(sh, x, w)
+        xb = layout.act_to_blocked(x).astype(np.float64)
+        wb = layout.filt_to_blocked(w).astype(np.float64)
+        xb = np.pad(xb, ((0, 0), (0, 0), (sh.pad, sh.pad), (sh.pad, sh.pad), (0, 0)))
+        Kb, Cb = wb.shape[:2]
+        ob = np.zeros((sh.N, Kb, sh.P, sh.Q, 16))
+        for n, kb, cb, oj, kj, ki in itertools.product(range(sh.N), range(Kb), range(Cb), range(sh.P),
+                                                       range(sh.R), range(sh.S)):
+            A = xb[n, cb, oj * sh.stride + kj, ki:ki + sh.stride * sh.Q:sh.stride, :]   # [Q][16 ifm]
+            ob[n, kb, oj] += A @ wb[kb, cb, kj, ki]                                      # [16 ifm][16 ofm]
+        np.testing.assert_allclose(layout.blocked_to_out(ob), out, rtol=0, atol=1e-11)
+
+
+def test_library_cross_check_float64(oracle_lib):
+    torch = pytest.importorskip("torch")
+    for sh, seed in ((ConvShape(2, 19, 11, 10, 32, 3, 3, 1, 1), 4), (ConvShape(1, 3, 20, 18, 16, 7, 7, 2, 3), 5),
+                     (ConvShape(2, 24, 8, 8, 48, 1, 1, 2, 0), 6)):
+        x, w = relu_like(sh, seed)
+        out, mag = oracle_lib.conv2d_fwd(sh, x, w)
+        want = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(),
+                                          stride=sh.stride, padding=sh.pad).numpy()
+        np.testing.assert_allclose(out, want, rtol=0, atol=1e-11)
+        wmag = torch.nn.functional.conv2d(torch.from_numpy(np.abs(x)).double(), torch.from_numpy(np.abs(w)).double(),
+                                          stride=sh.stride, padding=sh.pad).numpy()
+        np.testing.assert_allclose(mag, wmag, rtol=0, atol=1e-11)
+
+
+def test_point_and_range_queries_match_full(oracle_lib):
+    sh = ConvShape(3, 7, 9, 8, 16, 3, 3, 2, 1)
+    x, w = uniform_pm1(sh, 9)
+    out, mag = oracle_lib.conv2d_fwd(sh, x, w)
+    part, _ = oracle_lib.conv2d_fwd(sh, x, w, images=(1, 2))
+    np.testing.assert_array_equal(part[1], out[1])
+    assert not part[0].any() and not part[2].any()
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        n, k, p, q = rng.integers(sh.N), rng.integers(sh.K), rng.integers(sh.P), rng.integers(sh.Q)
+        o, m = oracle_lib.conv2d_fwd_point(sh, x, w, n, k, p, q)
+        assert o == out[n, k, p, q] and m == mag[n, k, p, q]
+
+
+def test_integer_inputs_are_exact(oracle_lib):
+    sh = ConvShape(1, 16, 6, 6, 16, 3, 3, 1, 1)
+    x, w = small_integers(sh, 5)
+    out, _ = oracle_lib.conv2d_fwd(sh, x, w)
+    assert np.array_equal(out, np.round(out))
+
+
+def test_normalised_error_metric(oracle_lib):
+    out = np.array([1.0, 0.0, -2.0])
+    mag = np.array([2.0, 0.0, 4.0])
+    assert oracle_lib.normalised_error(np.array([1.0, 0.0, -2.0]), out, mag) == 0.0
+    assert oracle_lib.normalised_error(np.array([1.5, 0.0, -2.0]), out, mag) == 0.25
+    assert oracle_lib.normalised_error(np.array([1.0, 1e-30, -2.0]), out, mag) == float("inf")
