@@ -1,0 +1,116 @@
+/*
+ * polysci_conv.h -- C ABI of the MI355X (gfx950) forward-convolution library.
+ *
+ * The library computes the forward 2-D convolution of the paper's Fig. 4 (Section 5,
+ * "The 2-D Convolution code") on the blocked tensor layouts that figure's index
+ * expressions define, as a grid of workgroups (the figure's outer loops) around a
+ * batch-reduce GEMM microkernel on the matrix cores (the figure's "GEMM operation"),
+ * plus the layout transforms into and out of the blocked layouts and the host-side
+ * tile-selection model (the analogue of Section 4's working-set ranking).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or keeps them.  They must be 16-byte aligned and must not alias.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call
+ *     only enqueues work on that stream and returns; there is no hidden synchronisation.
+ *   - Return value: PS_OK (0) or a negative ps_status.  A call that fails validation
+ *     launches nothing.  No C++ exception crosses this boundary.
+ *   - Descriptors are plain structs passed by pointer; the library copies what it needs.
+ *
+ * Layouts (B = 16, Cb = ceil(C/16), Kb = K/16; es = 4 bytes for PS_F32, 2 for PS_BF16)
+ *   activations, blocked : [N][Cb][H][W][16 c]              element size es
+ *   filters, blocked     : [Kb][Cb][R][S][16 c][16 k]       element size es   (k fastest)
+ *   outputs, blocked     : [N][Kb][P][Q][16 k]              always fp32
+ *   plain tensors        : NCHW, KCRS, NKPQ, dense
+ * Channel lanes c >= C of the blocked tensors hold +0.0.  K must be a multiple of 16.
+ * Padding is logical: the blocked input is H x W, out-of-image taps contribute zero.
+ * P = floor((H + 2*pad - R)/stride) + 1, Q likewise with W and S.
+ */
+#ifndef POLYSCI_CONV_H
+#define POLYSCI_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PS_OK = 0,
+    PS_EINVAL = -1,       /* null pointer, non-positive size, P or Q <= 0, misaligned pointer */
+    PS_EUNSUPPORTED = -2, /* K % 16 != 0, unknown dtype, tensor too large for 32-bit element offsets,
+                             tile not valid for this descriptor */
+    PS_EHIP = -3          /* the HIP runtime reported an error at launch */
+} ps_status;
+
+typedef enum { PS_F32 = 0, PS_BF16 = 1 } ps_dtype; /* element type of input and filter */
+
+/* Problem sizes of one convolution: the loop bounds and strides of Fig. 4 (nImg, nIfm, ifh,
+ * ifw, nOfm, kh, kw, STRIDE_H = STRIDE_W = stride) plus the symmetric zero padding that
+ * Section 2 lists among the layer parameters. */
+typedef struct {
+    int32_t N, C, H, W, K, R, S, stride, pad;
+    int32_t dtype; /* ps_dtype */
+} ps_conv_desc;
+
+/* One point of the outer-loop variant space (Section 4.2: tiling and interchange of the
+ * loops around the microkernel, with varied tile sizes), in GPU terms:
+ *   kt      output channels per workgroup tile (32, 64, 128 or 256)
+ *   mt      output pixels per workgroup tile, counted in the flattened (n, p, q) order
+ *   bpp     batch-reduce elements (c-block, r, s) staged in LDS per pipeline step
+ *   c_split workgroups that share one output tile, each reducing a contiguous slice of the
+ *           (c-block, r, s) range; > 1 accumulates with atomic adds into a cleared output
+ *   raster  launch order of tiles: 0 = output-channel tiles fastest, 1 = pixel tiles fastest
+ */
+typedef struct {
+    int32_t kt, mt, bpp, c_split, raster;
+} ps_tile;
+
+/* Output size of `d`.  PS_EINVAL if the descriptor is invalid. */
+int ps_out_dims(const ps_conv_desc *d, int32_t *P, int32_t *Q);
+
+/* Bytes of the blocked tensors of `d` (0 if the descriptor is invalid). */
+size_t ps_blocked_in_bytes(const ps_conv_desc *d);  /* N*Cb*H*W*16*es        */
+size_t ps_blocked_wt_bytes(const ps_conv_desc *d);  /* Kb*Cb*R*S*256*es      */
+size_t ps_blocked_out_bytes(const ps_conv_desc *d); /* N*Kb*P*Q*16*4         */
+
+/* ---- layout transforms (bit-exact permutations; Fig. 4 index expressions) -------------- */
+/* NCHW (N*C*H*W elements of size es) -> blocked activations; pad lanes written as +0.0. */
+int ps_nchw_to_blocked(const ps_conv_desc *d, const void *nchw, void *blk, void *stream);
+/* blocked activations -> NCHW (pad lanes dropped). */
+int ps_blocked_to_nchw(const ps_conv_desc *d, const void *blk, void *nchw, void *stream);
+/* KCRS -> blocked filters; pad c lanes written as +0.0. */
+int ps_kcrs_to_blocked(const ps_conv_desc *d, const void *kcrs, void *wblk, void *stream);
+/* blocked filters -> KCRS. */
+int ps_blocked_to_kcrs(const ps_conv_desc *d, const void *wblk, void *kcrs, void *stream);
+/* blocked fp32 output [N][Kb][P][Q][16] -> NKPQ fp32. */
+int ps_blocked_to_nkpq(const ps_conv_desc *d, const void *oblk, void *nkpq, void *stream);
+
+/* ---- forward convolution ------------------------------------------------------------- */
+/* out_blk = conv(in_blk, wt_blk) on blocked tensors; out_blk is overwritten (the "+=" of
+ * Fig. 4 applied to a cleared output).  The workgroup tile is the tile model's pick. */
+int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const void *wt_blk, void *out_blk,
+                  void *stream);
+/* Same with an explicit tile (autotune sweeps).  PS_EUNSUPPORTED if ps_tile_valid fails. */
+int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const void *in_blk,
+                       const void *wt_blk, void *out_blk, void *stream);
+
+/* ---- outer-loop variant space and its ranking (Section 4.2, Algorithm 2, Eq. 1) ------- */
+/* Number of candidate tiles the enumerator emits for `d` (negative ps_status on error). */
+int ps_tile_count(const ps_conv_desc *d);
+/* The idx-th candidate, 0 <= idx < ps_tile_count(d). */
+int ps_tile_get(const ps_conv_desc *d, int idx, ps_tile *t);
+/* PS_OK if `t` can run `d` (a compiled kernel shape exists and the split divides evenly). */
+int ps_tile_valid(const ps_conv_desc *d, const ps_tile *t);
+/* Modelled execution time of `t` on `d` in microseconds; negative if invalid. */
+double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t);
+/* The candidate with the lowest modelled time (k = 1 of the paper's top-k pick). */
+int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us);
+
+const char *ps_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLYSCI_CONV_H */

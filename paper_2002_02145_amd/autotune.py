@@ -1,0 +1,118 @@
+"""Exhaustive sweep over the tile enumerator's candidates, timed on the GPU.
+
+The paper runs its top-k ranked variants on the target and keeps the fastest, and reports, per
+layer, the slowest and fastest variant next to the one its model picked (Section 5.2, the
+"performance distribution" figures).  This module produces the same three numbers for the GPU
+variant space: every candidate of ``ps_tile_get`` is timed, and the model's pick
+(``ps_tile_select``) is located in that distribution.
+
+Timing uses HIP events on the launch stream; torch supplies memory and events only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import torch
+
+from . import binding as ps
+from . import workloads as wl
+
+
+def _buffers(desc: ps.ConvDesc, es: int, copies: int = 1):
+    tdt = torch.float32 if es == 4 else torch.bfloat16
+    g = torch.Generator(device="cuda").manual_seed(1)
+    sets = []
+    for _ in range(copies):
+        xb = torch.rand(ps.ps_blocked_in_bytes(desc) // es, device="cuda", generator=g).to(tdt)
+        wb = (torch.rand(ps.ps_blocked_wt_bytes(desc) // es, device="cuda", generator=g) - 0.5).to(tdt)
+        ob = torch.empty(ps.ps_blocked_out_bytes(desc) // 4, device="cuda", dtype=torch.float32)
+        sets.append((xb, wb, ob))
+    return sets
+
+
+def time_tile(desc: ps.ConvDesc, tile: ps.Tile | None, sets, warmup: int = 5, min_ms: float = 20.0,
+              max_iters: int = 2000) -> float:
+    """Mean microseconds per launch of one tile (None = the library's own pick)."""
+    stream = torch.cuda.current_stream()
+
+    def launch(i):
+        xb, wb, ob = sets[i % len(sets)]
+        if tile is None:
+            ps.ps_conv2d_fwd(desc, xb, wb, ob, stream)
+        else:
+            ps.ps_conv2d_fwd_tile(desc, tile, xb, wb, ob, stream)
+
+    for i in range(warmup):
+        launch(i)
+    torch.cuda.synchronize()
+    # size the repetition count from a first timed batch
+    iters = 5
+    while True:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(iters):
+            launch(i)
+        e1.record(stream)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1)
+        if ms >= min_ms or iters >= max_iters:
+            return ms * 1e3 / iters
+        iters = min(max_iters, max(iters * 2, int(iters * min_ms / max(ms, 1e-3)) + 1))
+
+
+def sweep(shape: wl.ConvShape, dtype: int = ps.PS_F32, min_ms: float = 20.0, cold: bool = False) -> dict:
+    desc = ps.ConvDesc.of(shape, dtype)
+    es = 4 if dtype == ps.PS_F32 else 2
+    per_set = ps.ps_blocked_in_bytes(desc) + ps.ps_blocked_wt_bytes(desc) + ps.ps_blocked_out_bytes(desc)
+    copies = max(1, -(-(600 << 20) // per_set)) if cold else 1
+    sets = _buffers(desc, es, copies)
+    rows = []
+    for i in range(ps.ps_tile_count(desc)):
+        t = ps.ps_tile_get(desc, i)
+        us = time_tile(desc, t, sets, min_ms=min_ms)
+        rows.append({"tile": t.as_tuple(), "us": us, "model_us": ps.ps_tile_cost_us(desc, t)})
+    pick, model_us = ps.ps_tile_select(desc)
+    best = min(rows, key=lambda r: r["us"])
+    worst = max(rows, key=lambda r: r["us"])
+    mine = next(r for r in rows if r["tile"] == pick.as_tuple())
+    gf = lambda us: shape.flops / us * 1e-3
+    return {
+        "layer": shape.name, "dtype": "f32" if dtype == ps.PS_F32 else "bf16", "candidates": len(rows),
+        "pick": pick.as_tuple(), "pick_us": mine["us"], "pick_model_us": model_us, "pick_gflops": gf(mine["us"]),
+        "best": best["tile"], "best_us": best["us"], "best_gflops": gf(best["us"]),
+        "worst": worst["tile"], "worst_us": worst["us"], "worst_gflops": gf(worst["us"]),
+        "pick_vs_best": best["us"] / mine["us"],
+        "rank_of_pick": sorted(r["us"] for r in rows).index(mine["us"]) + 1,
+        "rows": rows,
+    }
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--layers", default="sweep", help="sweep | cfg1 | cfg2 | cfg3a | cfg3b | comma list of layer names")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--min-ms", type=float, default=20.0)
+    ap.add_argument("--cold", action="store_true", help="rotate buffers so every launch streams from HBM")
+    ap.add_argument("--rows", action="store_true", help="include every candidate's time in the output")
+    ap.add_argument("--out", default=None)
+    a = ap.parse_args(argv)
+    named = {"cfg1": wl.CFG1, "cfg2": wl.CFG2, "cfg3a": wl.CFG3A, "cfg3b": wl.CFG3B}
+    named.update({l.name: l for l in wl.resnet50_layers()})
+    if a.layers == "sweep":
+        layers = wl.resnet50_layers() + [wl.CFG3B]
+    else:
+        layers = [named[n] for n in a.layers.split(",")]
+    dtype = ps.PS_F32 if a.dtype == "f32" else ps.PS_BF16
+    out = open(a.out, "w") if a.out else sys.stdout
+    for shape in layers:
+        r = sweep(shape, dtype, a.min_ms, a.cold)
+        if not a.rows:
+            r.pop("rows")
+        print(json.dumps(r), file=out, flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,176 @@
+"""ctypes binding of libpsconv.so: same names as the C ABI, argument marshalling only.
+
+Tensors are passed as anything with a ``data_ptr()`` method (torch tensors) or as raw integer
+device addresses.  The stream defaults to torch's current HIP stream.  Nothing here computes:
+every step runs in the library's kernels, and the import fails loudly if the library is absent.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpsconv.so")
+
+PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP = 0, -1, -2, -3
+PS_F32, PS_BF16 = 0, 1
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "C", "H", "W", "K", "R", "S", "stride", "pad", "dtype")]
+
+    @classmethod
+    def of(cls, shape, dtype: int = PS_F32) -> "ConvDesc":
+        """From any object with N, C, H, W, K, R, S, stride, pad attributes."""
+        return cls(shape.N, shape.C, shape.H, shape.W, shape.K, shape.R, shape.S,
+                   shape.stride, shape.pad, dtype)
+
+
+class Tile(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("kt", "mt", "bpp", "c_split", "raster")]
+
+    def as_tuple(self):
+        return (self.kt, self.mt, self.bpp, self.c_split, self.raster)
+
+    def __repr__(self):
+        return f"Tile(kt={self.kt}, mt={self.mt}, bpp={self.bpp}, c_split={self.c_split}, raster={self.raster})"
+
+
+class PsError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    dp = ctypes.POINTER(ConvDesc)
+    tp = ctypes.POINTER(Tile)
+    vp = ctypes.c_void_p
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    sig = {
+        "ps_out_dims": (ctypes.c_int, [dp, i32p, i32p]),
+        "ps_blocked_in_bytes": (ctypes.c_size_t, [dp]),
+        "ps_blocked_wt_bytes": (ctypes.c_size_t, [dp]),
+        "ps_blocked_out_bytes": (ctypes.c_size_t, [dp]),
+        "ps_nchw_to_blocked": (ctypes.c_int, [dp, vp, vp, vp]),
+        "ps_blocked_to_nchw": (ctypes.c_int, [dp, vp, vp, vp]),
+        "ps_kcrs_to_blocked": (ctypes.c_int, [dp, vp, vp, vp]),
+        "ps_blocked_to_kcrs": (ctypes.c_int, [dp, vp, vp, vp]),
+        "ps_blocked_to_nkpq": (ctypes.c_int, [dp, vp, vp, vp]),
+        "ps_conv2d_fwd": (ctypes.c_int, [dp, vp, vp, vp, vp]),
+        "ps_conv2d_fwd_tile": (ctypes.c_int, [dp, tp, vp, vp, vp, vp]),
+        "ps_tile_count": (ctypes.c_int, [dp]),
+        "ps_tile_get": (ctypes.c_int, [dp, ctypes.c_int, tp]),
+        "ps_tile_valid": (ctypes.c_int, [dp, tp]),
+        "ps_tile_cost_us": (ctypes.c_double, [dp, tp]),
+        "ps_tile_select": (ctypes.c_int, [dp, tp, ctypes.POINTER(ctypes.c_double)]),
+        "ps_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status: int) -> str:
+    return lib.ps_strerror(int(status)).decode()
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return 0
+    return int(t.data_ptr()) if hasattr(t, "data_ptr") else int(t)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def _check(status: int, what: str) -> None:
+    if status != PS_OK:
+        raise PsError(status, what)
+
+
+def ps_out_dims(desc: ConvDesc) -> tuple[int, int]:
+    P, Q = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib.ps_out_dims(ctypes.byref(desc), ctypes.byref(P), ctypes.byref(Q)), "ps_out_dims")
+    return P.value, Q.value
+
+
+def ps_blocked_in_bytes(desc: ConvDesc) -> int:
+    return int(lib.ps_blocked_in_bytes(ctypes.byref(desc)))
+
+
+def ps_blocked_wt_bytes(desc: ConvDesc) -> int:
+    return int(lib.ps_blocked_wt_bytes(ctypes.byref(desc)))
+
+
+def ps_blocked_out_bytes(desc: ConvDesc) -> int:
+    return int(lib.ps_blocked_out_bytes(ctypes.byref(desc)))
+
+
+def _transform(name: str):
+    fn = getattr(lib, name)
+
+    def call(desc: ConvDesc, src, dst, stream=None) -> None:
+        _check(fn(ctypes.byref(desc), _ptr(src), _ptr(dst), _stream(stream)), name)
+
+    call.__name__ = name
+    return call
+
+
+ps_nchw_to_blocked = _transform("ps_nchw_to_blocked")
+ps_blocked_to_nchw = _transform("ps_blocked_to_nchw")
+ps_kcrs_to_blocked = _transform("ps_kcrs_to_blocked")
+ps_blocked_to_kcrs = _transform("ps_blocked_to_kcrs")
+ps_blocked_to_nkpq = _transform("ps_blocked_to_nkpq")
+
+
+def ps_conv2d_fwd(desc: ConvDesc, in_blk, wt_blk, out_blk, stream=None) -> None:
+    _check(lib.ps_conv2d_fwd(ctypes.byref(desc), _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk), _stream(stream)),
+           "ps_conv2d_fwd")
+
+
+def ps_conv2d_fwd_tile(desc: ConvDesc, tile: Tile, in_blk, wt_blk, out_blk, stream=None) -> None:
+    _check(lib.ps_conv2d_fwd_tile(ctypes.byref(desc), ctypes.byref(tile), _ptr(in_blk), _ptr(wt_blk),
+                                  _ptr(out_blk), _stream(stream)), "ps_conv2d_fwd_tile")
+
+
+def ps_tile_count(desc: ConvDesc) -> int:
+    n = lib.ps_tile_count(ctypes.byref(desc))
+    if n < 0:
+        raise PsError(n, "ps_tile_count")
+    return n
+
+
+def ps_tile_get(desc: ConvDesc, idx: int) -> Tile:
+    t = Tile()
+    _check(lib.ps_tile_get(ctypes.byref(desc), int(idx), ctypes.byref(t)), "ps_tile_get")
+    return t
+
+
+def ps_tile_valid(desc: ConvDesc, tile: Tile) -> bool:
+    return lib.ps_tile_valid(ctypes.byref(desc), ctypes.byref(tile)) == PS_OK
+
+
+def ps_tile_cost_us(desc: ConvDesc, tile: Tile) -> float:
+    return float(lib.ps_tile_cost_us(ctypes.byref(desc), ctypes.byref(tile)))
+
+
+def ps_tile_select(desc: ConvDesc) -> tuple[Tile, float]:
+    t, us = Tile(), ctypes.c_double()
+    _check(lib.ps_tile_select(ctypes.byref(desc), ctypes.byref(t), ctypes.byref(us)), "ps_tile_select")
+    return t, us.value

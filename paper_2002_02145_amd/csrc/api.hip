@@ -1,0 +1,177 @@
+// C ABI entry points: descriptor validation, size queries, convolution launch.
+#include <mutex>
+
+#include "conv_fwd_kernel.h"
+
+namespace ps {
+
+const ShapeEntry *f32_shapes(int *count);
+const ShapeEntry *bf16_shapes(int *count);
+
+int make_dims(const ps_conv_desc *d, Dims *o)
+{
+    if (!d || !o) return PS_EINVAL;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 ||
+        d->stride <= 0 || d->pad < 0)
+        return PS_EINVAL;
+    if (d->dtype != PS_F32 && d->dtype != PS_BF16) return PS_EUNSUPPORTED;
+    const long long hp = (long long)d->H + 2LL * d->pad - d->R, wp = (long long)d->W + 2LL * d->pad - d->S;
+    if (hp < 0 || wp < 0) return PS_EINVAL;
+    if (d->K % kBlock != 0) return PS_EUNSUPPORTED;
+    o->N = d->N; o->C = d->C; o->H = d->H; o->W = d->W; o->K = d->K; o->R = d->R; o->S = d->S;
+    o->stride = d->stride; o->pad = d->pad; o->dtype = d->dtype;
+    o->es = d->dtype == PS_F32 ? 4 : 2;
+    o->P = (int)(hp / d->stride) + 1;
+    o->Q = (int)(wp / d->stride) + 1;
+    o->Cb = (d->C + kBlock - 1) / kBlock;
+    o->Kb = d->K / kBlock;
+    const long long nb = (long long)o->Cb * d->R * d->S;
+    o->M = (long long)d->N * o->P * o->Q;
+    // 32-bit byte offsets inside the kernels: every blocked tensor must stay below 2 GiB
+    const long long lim = (1LL << 31) - 1;
+    const long long in_b = (long long)d->N * o->Cb * d->H * d->W * kBlock * o->es;
+    const long long wt_b = (long long)o->Kb * nb * kBlock * kBlock * o->es;
+    const long long out_b = o->M * d->K * 4;
+    if (nb > (1 << 24) || in_b > lim || wt_b > lim || out_b > lim) return PS_EUNSUPPORTED;
+    o->NB = (int)nb;
+    return PS_OK;
+}
+
+const ShapeEntry *find_shape(int dtype, int kt, int mt, int bpp)
+{
+    int n = 0;
+    const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
+    for (int i = 0; i < n; ++i)
+        if (tab[i].kt == kt && tab[i].mt == mt && tab[i].bpp == bpp) return &tab[i];
+    return nullptr;
+}
+
+struct ShapeInfo {
+    int kt, mt, bpp, threads, lds_bytes;
+};
+
+int list_shapes(int dtype, ShapeInfo *out, int cap)
+{
+    int n = 0;
+    const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
+    n = n < cap ? n : cap;
+    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].bpp, tab[i].threads, tab[i].lds_bytes};
+    return n;
+}
+
+int tile_valid(const Dims &dm, const ps_tile &t)
+{
+    if (t.kt <= 0 || t.mt <= 0 || t.bpp <= 0 || t.c_split <= 0 || (t.raster != 0 && t.raster != 1))
+        return PS_EUNSUPPORTED;
+    if (!find_shape(dm.dtype, t.kt, t.mt, t.bpp)) return PS_EUNSUPPORTED;
+    // output channels are padded to whole 32-wide MFMA tiles at most: a larger kt would only add waste
+    if ((dm.K + t.kt - 1) / t.kt * t.kt != (dm.K + 31) / 32 * 32) return PS_EUNSUPPORTED;
+    if (dm.NB % t.c_split != 0) return PS_EUNSUPPORTED;
+    const long long n_mt = (dm.M + t.mt - 1) / t.mt;
+    if (n_mt * ((dm.K + t.kt - 1) / t.kt) * t.c_split > (1LL << 30)) return PS_EUNSUPPORTED;
+    return PS_OK;
+}
+
+int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, hipStream_t st)
+{
+    int rc = tile_valid(dm, t);
+    if (rc != PS_OK) return rc;
+    const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.bpp);
+    ConvArgs a;
+    a.in = in; a.wt = wt; a.out = out;
+    a.H = dm.H; a.W = dm.W; a.Cb = dm.Cb; a.Kb = dm.Kb; a.R = dm.R; a.S = dm.S;
+    a.stride = dm.stride; a.pad = dm.pad; a.Q = dm.Q;
+    a.PQ = dm.P * dm.Q;
+    a.M = (int)dm.M;
+    a.NB = dm.NB;
+    a.c_split = t.c_split;
+    a.nb_split = dm.NB / t.c_split;
+    a.n_mt = (int)((dm.M + t.mt - 1) / t.mt);
+    a.n_kt = (dm.K + t.kt - 1) / t.kt;
+    a.raster = t.raster;
+    a.in_bytes = (unsigned)((size_t)dm.N * dm.Cb * dm.H * dm.W * kBlock * dm.es);
+    a.wt_bytes = (unsigned)((size_t)dm.Kb * dm.NB * kBlock * kBlock * dm.es);
+    if (t.c_split > 1) {
+        rc = launch_fill_zero(out, (size_t)dm.M * dm.K, st);
+        if (rc != PS_OK) return rc;
+    }
+    sh->launch(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace ps
+
+using namespace ps;
+
+extern "C" int ps_out_dims(const ps_conv_desc *d, int32_t *P, int32_t *Q)
+{
+    Dims dm;
+    if (!P || !Q) return PS_EINVAL;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    *P = dm.P;
+    *Q = dm.Q;
+    return PS_OK;
+}
+
+extern "C" size_t ps_blocked_in_bytes(const ps_conv_desc *d)
+{
+    Dims dm;
+    if (make_dims(d, &dm) != PS_OK) return 0;
+    return (size_t)dm.N * dm.Cb * dm.H * dm.W * kBlock * dm.es;
+}
+
+extern "C" size_t ps_blocked_wt_bytes(const ps_conv_desc *d)
+{
+    Dims dm;
+    if (make_dims(d, &dm) != PS_OK) return 0;
+    return (size_t)dm.Kb * dm.Cb * dm.R * dm.S * kBlock * kBlock * dm.es;
+}
+
+extern "C" size_t ps_blocked_out_bytes(const ps_conv_desc *d)
+{
+    Dims dm;
+    if (make_dims(d, &dm) != PS_OK) return 0;
+    return (size_t)dm.M * dm.K * 4;
+}
+
+extern "C" int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
+                                  void *out_blk, void *stream)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!t || !in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk)) return PS_EINVAL;
+    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, (hipStream_t)stream);
+}
+
+extern "C" int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const void *wt_blk, void *out_blk,
+                             void *stream)
+{
+    ps_tile t;
+    double us;
+    int rc = ps_tile_select(d, &t, &us);
+    if (rc != PS_OK) return rc;
+    return ps_conv2d_fwd_tile(d, &t, in_blk, wt_blk, out_blk, stream);
+}
+
+extern "C" int ps_tile_valid(const ps_conv_desc *d, const ps_tile *t)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!t) return PS_EINVAL;
+    return tile_valid(dm, *t);
+}
+
+extern "C" const char *ps_strerror(int status)
+{
+    switch (status) {
+    case PS_OK: return "ok";
+    case PS_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, empty output)";
+    case PS_EUNSUPPORTED: return "unsupported (K not a multiple of 16, unknown dtype, tensor over 2 GiB, or tile not valid)";
+    case PS_EHIP: return "HIP runtime error at kernel launch";
+    default: return "unknown status";
+    }
+}

@@ -1,0 +1,40 @@
+// Internal helpers shared by the translation units of the GPU library (never installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "polysci_conv.h"
+
+namespace ps {
+
+constexpr int kBlock = 16;  // channel block B of the blocked layouts
+
+struct Dims {
+    int N, C, H, W, K, R, S, stride, pad;
+    int P, Q;    // output size
+    int Cb, Kb;  // channel blocks
+    int NB;      // batch-reduce length Cb*R*S
+    long long M; // flattened output pixels N*P*Q
+    int es;      // element size of input/filter in bytes
+    int dtype;
+};
+
+// Validates a descriptor and derives the sizes every entry point needs.
+int make_dims(const ps_conv_desc *d, Dims *out);
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? PS_OK : PS_EHIP; }
+
+// conv_fwd_*.hip
+int launch_conv_f32(const Dims &dm, const ps_tile &t, const float *in, const float *wt, float *out,
+                    hipStream_t stream);
+int launch_conv_bf16(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out,
+                     hipStream_t stream);
+bool conv_shape_compiled(int dtype, int kt, int mt, int bpp);
+int conv_shape_lds_bytes(int dtype, int kt, int mt, int bpp);
+int conv_shape_threads(int dtype, int kt, int mt, int bpp);
+int launch_fill_zero(float *p, size_t n, hipStream_t stream);
+
+}  // namespace ps

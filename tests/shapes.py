@@ -1,0 +1,16 @@
+"""Small convolution shapes that exercise the edges of the tiling (shared by host and GPU tests)."""
+from paper_2002_02145_amd.workloads import ConvShape
+
+EDGE_SHAPES = [
+    ConvShape(1, 64, 14, 14, 64, 3, 3, 1, 1, "cfg1"),
+    ConvShape(3, 32, 7, 7, 64, 3, 3, 1, 1, "tiles_cross_images"),      # 49 px per image: tiles span images
+    ConvShape(2, 3, 23, 19, 32, 7, 7, 2, 3, "stem_like_C3"),            # ragged C, big filter, stride 2
+    ConvShape(2, 48, 9, 11, 32, 1, 1, 2, 0, "1x1_stride2_odd"),
+    ConvShape(1, 20, 6, 5, 16, 2, 3, 1, 1, "non_square_filter"),        # K = 16: half an MFMA tile
+    ConvShape(5, 16, 5, 5, 128, 1, 1, 1, 0, "1x1_small"),
+    ConvShape(1, 16, 1, 1, 16, 1, 1, 1, 0, "single_pixel"),
+    ConvShape(2, 16, 4, 4, 32, 3, 3, 3, 2, "stride3_pad2"),
+    ConvShape(1, 32, 12, 12, 256, 3, 3, 1, 0, "no_pad_K256"),
+    ConvShape(2, 16, 6, 6, 48, 3, 3, 1, 1, "K48_ragged_tile"),
+    ConvShape(1, 80, 3, 3, 96, 1, 1, 1, 0, "five_blocks_prime_batch"),  # batch-reduce length 5
+]

@@ -1,0 +1,94 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared
+symbol, validates descriptors, and the tile enumerator/model behave sanely."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2002_02145_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ps():
+    from paper_2002_02145_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(ps):
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in os.listdir(inc):
+        text = open(os.path.join(inc, f)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(ps_[a-z0-9_]+)\s*\(", text))
+    assert len(names) >= 17
+    raw = ctypes.CDLL(ps.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(raw, n), f"{n} declared in include/ but not exported"
+        assert hasattr(ps, n) or n == "ps_strerror", f"{n} has no Python binding of the same name"
+
+
+def test_sizes_and_dims(ps):
+    d = ps.ConvDesc.of(wl.CFG3B)
+    assert ps.ps_out_dims(d) == (14, 14)
+    assert ps.ps_blocked_in_bytes(d) == 28 * 512 * 28 * 28 * 4
+    assert ps.ps_blocked_wt_bytes(d) == 1024 * 512 * 4
+    assert ps.ps_blocked_out_bytes(d) == 28 * 1024 * 14 * 14 * 4
+    stem = wl.resnet50_layers()[-1]
+    d = ps.ConvDesc.of(stem)
+    assert ps.ps_out_dims(d) == (112, 112)
+    assert ps.ps_blocked_in_bytes(d) == 28 * 16 * 224 * 224 * 4          # C = 3 padded to one block
+    assert ps.ps_blocked_wt_bytes(d) == 64 * 16 * 49 * 4
+    d = ps.ConvDesc.of(stem, ps.PS_BF16)
+    assert ps.ps_blocked_in_bytes(d) == 28 * 16 * 224 * 224 * 2
+    assert ps.ps_blocked_out_bytes(d) == 28 * 64 * 112 * 112 * 4         # output stays fp32
+
+
+def test_descriptor_validation(ps):
+    ok = wl.ConvShape(1, 16, 8, 8, 16, 3, 3, 1, 1)
+    for field, val, status in [("N", 0, ps.PS_EINVAL), ("C", -1, ps.PS_EINVAL), ("stride", 0, ps.PS_EINVAL),
+                               ("pad", -1, ps.PS_EINVAL), ("R", 11, ps.PS_EINVAL), ("K", 24, ps.PS_EUNSUPPORTED)]:
+        d = ps.ConvDesc.of(ok)
+        setattr(d, field, val)
+        with pytest.raises(ps.PsError) as e:
+            ps.ps_out_dims(d)
+        assert e.value.status == status, field
+        assert ps.ps_blocked_in_bytes(d) == 0
+    d = ps.ConvDesc.of(ok, 7)
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_out_dims(d)
+    assert e.value.status == ps.PS_EUNSUPPORTED
+    huge = ps.ConvDesc.of(wl.ConvShape(512, 1024, 224, 224, 16, 1, 1, 1, 0))     # > 2 GiB input
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_out_dims(huge)
+    assert e.value.status == ps.PS_EUNSUPPORTED
+    assert "unsupported" in ps.strerror(ps.PS_EUNSUPPORTED)
+    assert ps.strerror(ps.PS_OK) == "ok"
+
+
+def test_tile_enumerator_and_model(ps):
+    from shapes import EDGE_SHAPES
+    for shape in wl.resnet50_layers() + [wl.CFG1, wl.CFG3B] + EDGE_SHAPES:
+        d = ps.ConvDesc.of(shape)
+        n = ps.ps_tile_count(d)
+        assert n > 0
+        tiles = [ps.ps_tile_get(d, i) for i in range(n)]
+        assert len({t.as_tuple() for t in tiles}) == n, "duplicate candidates"
+        nb = -(-shape.C // 16) * shape.R * shape.S
+        for t in tiles:
+            assert ps.ps_tile_valid(d, t)
+            assert nb % t.c_split == 0
+            assert ps.ps_tile_cost_us(d, t) > 0
+        best, us = ps.ps_tile_select(d)
+        costs = [ps.ps_tile_cost_us(d, t) for t in tiles]
+        assert us == pytest.approx(min(costs))
+        assert best.as_tuple() in {t.as_tuple() for t in tiles}
+        # no variant can be modelled faster than the matrix cores allow
+        assert us * 1e-6 >= shape.flops_issued / 157.3e12 * 0.999
+        with pytest.raises(ps.PsError):
+            ps.ps_tile_get(d, n)
+    assert not ps.ps_tile_valid(ps.ConvDesc.of(wl.CFG1), ps.Tile(128, 128, 2, 1, 0))   # K = 64 < kt
+    assert ps.ps_tile_cost_us(ps.ConvDesc.of(wl.CFG1), ps.Tile(128, 128, 2, 1, 0)) < 0

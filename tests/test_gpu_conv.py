@@ -1,0 +1,138 @@
+"""GPU forward convolution (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances (stated by the task's accuracy target): max |gpu - oracle| / sum|x*w| <= 1e-4 for fp32
+inputs and <= 2e-2 for bf16 inputs with fp32 accumulation; outputs whose magnitude sum is zero must
+be exactly zero; integer-valued inputs must reproduce the exact result."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2002_02145_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-4, 1: 2e-2}
+
+
+def _prep(shape, gen, seed, dtype):
+    x, w = gen(shape, seed)
+    if dtype == 1:
+        x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
+    return x, w
+
+
+def _dtypes():
+    from paper_2002_02145_amd import binding as ps
+    out = [0]
+    d = ps.ConvDesc.of(wl.CFG1, ps.PS_BF16)
+    if ps.lib.ps_tile_count(d) > 0:
+        out.append(1)
+    return out
+
+
+from shapes import EDGE_SHAPES
+
+
+@pytest.mark.parametrize("shape", EDGE_SHAPES, ids=lambda s: s.name)
+def test_every_candidate_tile_matches_oracle(shape):
+    """Each tile the enumerator can emit must itself be correct (edge tiles, ragged tails, splits)."""
+    from gpu_util import run_conv, all_tiles
+    for dtype in _dtypes():
+        x, w = _prep(shape, wl.uniform_pm1, 1, dtype)
+        out, mag = oracle.conv2d_fwd(shape, x, w)
+        tiles = all_tiles(shape, dtype)
+        assert tiles, "enumerator produced no candidate"
+        for t in tiles:
+            got = run_conv(shape, x, w, dtype, t)
+            err = oracle.normalised_error(got, out, mag)
+            assert err <= TOL[dtype], f"{shape.name} dtype={dtype} {t}: err {err}"
+        got = run_conv(shape, x, w, dtype)          # the model's pick through ps_conv2d_fwd
+        assert oracle.normalised_error(got, out, mag) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("shape", EDGE_SHAPES[:5], ids=lambda s: s.name)
+def test_integer_inputs_reproduce_exact_result(shape):
+    from gpu_util import run_conv, all_tiles
+    for dtype in _dtypes():
+        x, w = wl.small_integers(shape, 7)
+        out, _ = oracle.conv2d_fwd(shape, x, w)
+        for t in all_tiles(shape, dtype):
+            got = run_conv(shape, x, w, dtype, t)
+            assert np.array_equal(got.astype(np.float64), out), f"{shape.name} dtype={dtype} {t}"
+
+
+def test_zero_magnitude_outputs_are_exact_zero():
+    from gpu_util import run_conv
+    shape = wl.ConvShape(2, 32, 10, 10, 32, 3, 3, 1, 1)
+    x, w = wl.uniform_pm1(shape, 3)
+    x[1] = 0.0                      # a whole image of zeros
+    w[5] = 0.0                      # a whole output channel of zeros
+    out, mag = oracle.conv2d_fwd(shape, x, w)
+    got = run_conv(shape, x, w)
+    assert not got[1].any() and not got[:, 5].any()
+    assert oracle.normalised_error(got, out, mag) <= 1e-4
+
+
+def test_output_is_overwritten_not_accumulated():
+    from gpu_util import run_conv
+    shape = wl.CFG1
+    x, w = wl.uniform_pm1(shape, 1)
+    out, mag = oracle.conv2d_fwd(shape, x, w)
+    for poison in (1e30, float("nan")):
+        got = run_conv(shape, x, w, poison=poison)
+        assert oracle.normalised_error(got, out, mag) <= 1e-4
+
+
+FULL = [(wl.CFG2, 2), (wl.CFG3A, 3), (wl.CFG3B, 4)]
+
+
+@pytest.mark.parametrize("shape,seed", FULL, ids=lambda v: getattr(v, "name", str(v)))
+def test_full_size_configs_fp32(shape, seed):
+    """Benchmark sizes, launch configuration the benchmark times (the model's pick): two whole images
+    plus random samples of the rest against the oracle."""
+    from gpu_util import run_conv
+    x, w = wl.relu_like(shape, seed)
+    got = run_conv(shape, x, w)
+    out, mag = oracle.conv2d_fwd(shape, x, w, images=(0, 1))
+    assert oracle.normalised_error(got[:1], out[:1], mag[:1]) <= 1e-4
+    n = shape.N - 1
+    out, mag = oracle.conv2d_fwd(shape, x, w, images=(n, n + 1))
+    assert oracle.normalised_error(got[n:], out[n:], mag[n:]) <= 1e-4
+    rng = np.random.default_rng(seed)
+    for _ in range(300):
+        n, k, p, q = (int(rng.integers(v)) for v in (shape.N, shape.K, shape.P, shape.Q))
+        o, m = oracle.conv2d_fwd_point(shape, x, w, n, k, p, q)
+        assert abs(got[n, k, p, q] - o) <= 1e-4 * m
+
+
+def test_resnet50_sweep_fp32():
+    from gpu_util import run_conv
+    for i, shape in enumerate(wl.resnet50_layers()):
+        x, w = wl.relu_like(shape, wl.sweep_seed(i))
+        got = run_conv(shape, x, w)
+        n = i % shape.N
+        out, mag = oracle.conv2d_fwd(shape, x, w, images=(n, n + 1))
+        err = oracle.normalised_error(got[n:n + 1], out[n:n + 1], mag[n:n + 1])
+        assert err <= 1e-4, f"{shape.name}: {err}"
+        rng = np.random.default_rng(i)
+        for _ in range(100):
+            nn, k, p, q = (int(rng.integers(v)) for v in (shape.N, shape.K, shape.P, shape.Q))
+            o, m = oracle.conv2d_fwd_point(shape, x, w, nn, k, p, q)
+            assert abs(got[nn, k, p, q] - o) <= 1e-4 * m, shape.name
+
+
+def test_invalid_arguments_launch_nothing():
+    import torch
+    from paper_2002_02145_amd import binding as ps
+    d = ps.ConvDesc.of(wl.CFG1)
+    buf = torch.zeros(1 << 16, device="cuda:0")
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_conv2d_fwd(d, 0, buf, buf)
+    assert e.value.status == ps.PS_EINVAL
+    bad_tile = ps.Tile(48, 128, 2, 1, 0)
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_conv2d_fwd_tile(d, bad_tile, buf, buf, buf)
+    assert e.value.status == ps.PS_EUNSUPPORTED
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_conv2d_fwd_tile(d, ps.Tile(64, 128, 2, 5, 0), buf, buf, buf)   # 36 batch elements % 5 != 0
+    assert e.value.status == ps.PS_EUNSUPPORTED
