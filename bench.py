@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the forward-convolution hot path on one MI355X.
+
+A step is one forward convolution of the headline layer on blocked tensors that are already
+resident in HBM: the region the paper times (its Fig. 4 loop nest runs on blocked arrays, Section 5)
+and the one the metric 2*N*K*P*Q*C*R*S / t is defined on.  The layout transforms are one-off per
+network input / per layer; their bandwidth is reported beside the headline, not inside it.
+
+Prints ONE JSON line.  Extra keys: ``roofline`` (dominant kernel against the fp32 MFMA peak, timed
+with HIP events on the launch stream), ``cpu_baseline`` (the CPU oracle on the host cores),
+``layers`` (every ResNet-50-shaped layer with the tile model's pick), ``transforms``.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+HBM_PEAK_GBS = 8000.0
+
+
+def _time_steps(fn, steps: int, warmup: int):
+    """(wall ms per step, event ms per step) for `steps` back-to-back launches of fn()."""
+    import torch
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        fn()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-layers", action="store_true", help="skip the per-layer sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args(argv)
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (convolution forward needs no exchange between "
+              "GPUs; see DESIGN.md for how it would shard); rerun with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2002_02145_amd import binding as ps
+    from paper_2002_02145_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    dtype = ps.PS_F32 if a.dtype == "f32" else ps.PS_BF16
+    tdt = torch.float32 if a.dtype == "f32" else torch.bfloat16
+    es = 4 if a.dtype == "f32" else 2
+
+    # ---- headline workload: ResNet-50-shaped 3x3, N=28, C=K=64, 56x56 -------------------------
+    shape = wl.CFG2
+    x, w = wl.relu_like(shape, 2)
+    if a.dtype == "bf16":
+        x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
+    d = ps.ConvDesc.of(shape, dtype)
+    xd = torch.from_numpy(x).to(tdt).to(dev)
+    wd = torch.from_numpy(w).to(tdt).to(dev)
+    xb = torch.empty(ps.ps_blocked_in_bytes(d) // es, dtype=tdt, device=dev)
+    wb = torch.empty(ps.ps_blocked_wt_bytes(d) // es, dtype=tdt, device=dev)
+    ob = torch.empty(ps.ps_blocked_out_bytes(d) // 4, dtype=torch.float32, device=dev)
+    y = torch.empty((shape.N, shape.K, shape.P, shape.Q), dtype=torch.float32, device=dev)
+    ps.ps_nchw_to_blocked(d, xd, xb)
+    ps.ps_kcrs_to_blocked(d, wd, wb)
+    tile, model_us = ps.ps_tile_select(d)
+
+    wall_ms, ev_ms = _time_steps(lambda: ps.ps_conv2d_fwd(d, xb, wb, ob), a.steps, a.warmup)
+    gflops = shape.flops / (wall_ms * 1e-3) * 1e-9
+    kernel_tflops = shape.flops / (ev_ms * 1e-3) * 1e-12
+
+    # transforms: bytes moved (read + write) per call
+    tr = {}
+    for name, fn, nbytes in (
+            ("nchw_to_blocked", lambda: ps.ps_nchw_to_blocked(d, xd, xb), 2 * xb.numel() * es),
+            ("blocked_to_nkpq", lambda: ps.ps_blocked_to_nkpq(d, ob, y), 2 * ob.numel() * 4),
+            ("kcrs_to_blocked", lambda: ps.ps_kcrs_to_blocked(d, wd, wb), 2 * wb.numel() * es)):
+        _, ms = _time_steps(fn, 50, 5)
+        tr[name] = {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1)}
+    _, e2e_ms = _time_steps(lambda: (ps.ps_nchw_to_blocked(d, xd, xb), ps.ps_conv2d_fwd(d, xb, wb, ob),
+                                     ps.ps_blocked_to_nkpq(d, ob, y)), 50, 5)
+
+    # ---- correctness of what was timed, and the CPU baseline, on the same inputs ----------------
+    ps.ps_blocked_to_nkpq(d, ob, y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    cpu = None
+    checked = None
+    if not a.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        t0 = time.perf_counter()
+        out, mag = oracle.conv2d_fwd(shape, x, w)
+        dt = time.perf_counter() - t0
+        err = oracle.normalised_error(got, out, mag)
+        tol = 1e-4 if a.dtype == "f32" else 2e-2
+        checked = {"max_normalised_error": err, "tolerance": tol, "pass": bool(err <= tol)}
+        cpu = {"value": round(shape.flops / dt * 1e-9, 3), "unit": "GFLOP/s", "cores": oracle.threads(),
+               "kind": "oracle", "sample": f"whole layer {shape.name} (all {shape.N} images), 1 repetition, "
+                                          f"{dt:.2f} s; fp64 seven-loop definition, OpenMP over (n, k)"}
+
+    # ---- every ResNet-50-shaped layer with the model's pick --------------------------------------
+    layers = []
+    if not a.no_layers:
+        g = torch.Generator(device=dev).manual_seed(7)
+        for L in wl.resnet50_layers() + [wl.CFG3B]:
+            dl = ps.ConvDesc.of(L, dtype)
+            xi = torch.rand(ps.ps_blocked_in_bytes(dl) // es, device=dev, generator=g).to(tdt)
+            wi = ((torch.rand(ps.ps_blocked_wt_bytes(dl) // es, device=dev, generator=g) - 0.5) * 0.1).to(tdt)
+            oi = torch.empty(ps.ps_blocked_out_bytes(dl) // 4, device=dev, dtype=torch.float32)
+            t, _ = ps.ps_tile_select(dl)
+            reps = max(20, min(300, int(20e-3 / (L.flops_issued / (PEAK_TFLOPS[a.dtype] * 1e12 * 0.3)))))
+            _, ms = _time_steps(lambda: ps.ps_conv2d_fwd(dl, xi, wi, oi), reps, 5)
+            tf = L.flops / (ms * 1e-3) * 1e-12
+            layers.append({"layer": L.name, "us": round(ms * 1e3, 2), "TFLOP/s": round(tf, 2),
+                           "frac_mfma_peak": round(tf / PEAK_TFLOPS[a.dtype], 4),
+                           "frac_mfma_peak_issued": round(L.flops_issued / (ms * 1e-3) * 1e-12 / PEAK_TFLOPS[a.dtype], 4),
+                           "tile": list(t.as_tuple())})
+            del xi, wi, oi
+        tot_flop = sum(L.flops for L in wl.resnet50_layers())
+        tot_s = sum(l["us"] for l in layers[:len(wl.resnet50_layers())]) * 1e-6
+        agg = {"flop_weighted_TFLOP/s": round(tot_flop / tot_s * 1e-12, 2),
+               "geomean_TFLOP/s": round(math.exp(sum(math.log(l["TFLOP/s"]) for l in layers[:13]) / 13), 2)}
+    else:
+        agg = None
+
+    peak = PEAK_TFLOPS[a.dtype]
+    line = {
+        "metric": "conv fwd GFLOP/s (2*N*K*P*Q*C*R*S/t), 1 GPU",
+        "value": round(gflops, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": a.dtype,
+        "data": "synthetic (seeded: input U[0,1), filter N(0, sqrt(2/(C*R*S))))",
+        "config": {"workload": f"ResNet-50-shaped 3x3 conv fwd: N={shape.N} C={shape.C} K={shape.K} "
+                               f"H=W={shape.H} R=S=3 stride 1 pad 1, blocked 16c layouts, tensors resident in HBM",
+                   "tile": list(tile.as_tuple()), "tile_model_us": round(model_us, 2),
+                   "timing": "warm (same buffers every step)"},
+        "frac_mfma_peak": round(gflops * 1e-3 / peak, 4),
+        "roofline": {"bound": "mfma", "achieved": round(kernel_tflops, 2), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(kernel_tflops / peak, 4), "traffic": None,
+                     "kernel": "conv_fwd_%s_kernel<kt=%d,mt=%d,ring=%d>" % (a.dtype, tile.kt, tile.mt, tile.ring),
+                     "kernel_us": round(ev_ms * 1e3, 2), "flop_per_launch": shape.flops},
+        "cpu_baseline": cpu,
+        "checked_against_oracle": checked,
+        "transforms": tr,
+        "with_layout_transforms_GFLOP/s": round(shape.flops / (e2e_ms * 1e-3) * 1e-9, 1),
+        "layers": layers,
+        "layers_aggregate": agg,
+        "paper_context": "paper: 2448 GFLOP/s geomean on ResNet-50 layers, 28-core Xeon 8280, fp32 (Table 1)",
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

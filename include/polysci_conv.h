@@ -58,13 +58,14 @@ typedef struct {
  * loops around the microkernel, with varied tile sizes), in GPU terms:
  *   kt      output channels per workgroup tile (32, 64, 128 or 256)
  *   mt      output pixels per workgroup tile, counted in the flattened (n, p, q) order
- *   bpp     batch-reduce elements (c-block, r, s) staged in LDS per pipeline step
+ *   ring    batch-reduce elements (c-block, r, s) resident in the LDS ring, i.e. how far ahead of the
+ *           matrix cores the global loads run (2 or 4)
  *   c_split workgroups that share one output tile, each reducing a contiguous slice of the
  *           (c-block, r, s) range; > 1 accumulates with atomic adds into a cleared output
  *   raster  launch order of tiles: 0 = output-channel tiles fastest, 1 = pixel tiles fastest
  */
 typedef struct {
-    int32_t kt, mt, bpp, c_split, raster;
+    int32_t kt, mt, ring, c_split, raster;
 } ps_tile;
 
 /* Output size of `d`.  PS_EINVAL if the descriptor is invalid. */

@@ -29,13 +29,13 @@ class ConvDesc(ctypes.Structure):
 
 
 class Tile(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("kt", "mt", "bpp", "c_split", "raster")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("kt", "mt", "ring", "c_split", "raster")]
 
     def as_tuple(self):
-        return (self.kt, self.mt, self.bpp, self.c_split, self.raster)
+        return (self.kt, self.mt, self.ring, self.c_split, self.raster)
 
     def __repr__(self):
-        return f"Tile(kt={self.kt}, mt={self.mt}, bpp={self.bpp}, c_split={self.c_split}, raster={self.raster})"
+        return f"Tile(kt={self.kt}, mt={self.mt}, ring={self.ring}, c_split={self.c_split}, raster={self.raster})"
 
 
 class PsError(RuntimeError):

@@ -37,17 +37,17 @@ int make_dims(const ps_conv_desc *d, Dims *o)
     return PS_OK;
 }
 
-const ShapeEntry *find_shape(int dtype, int kt, int mt, int bpp)
+const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 {
     int n = 0;
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     for (int i = 0; i < n; ++i)
-        if (tab[i].kt == kt && tab[i].mt == mt && tab[i].bpp == bpp) return &tab[i];
+        if (tab[i].kt == kt && tab[i].mt == mt && tab[i].ring == ring) return &tab[i];
     return nullptr;
 }
 
 struct ShapeInfo {
-    int kt, mt, bpp, threads, lds_bytes;
+    int kt, mt, ring, threads, lds_bytes;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -55,15 +55,15 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     int n = 0;
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     n = n < cap ? n : cap;
-    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].bpp, tab[i].threads, tab[i].lds_bytes};
+    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes};
     return n;
 }
 
 int tile_valid(const Dims &dm, const ps_tile &t)
 {
-    if (t.kt <= 0 || t.mt <= 0 || t.bpp <= 0 || t.c_split <= 0 || (t.raster != 0 && t.raster != 1))
+    if (t.kt <= 0 || t.mt <= 0 || t.ring <= 0 || t.c_split <= 0 || (t.raster != 0 && t.raster != 1))
         return PS_EUNSUPPORTED;
-    if (!find_shape(dm.dtype, t.kt, t.mt, t.bpp)) return PS_EUNSUPPORTED;
+    if (!find_shape(dm.dtype, t.kt, t.mt, t.ring)) return PS_EUNSUPPORTED;
     // output channels are padded to whole 32-wide MFMA tiles at most: a larger kt would only add waste
     if ((dm.K + t.kt - 1) / t.kt * t.kt != (dm.K + 31) / 32 * 32) return PS_EUNSUPPORTED;
     if (dm.NB % t.c_split != 0) return PS_EUNSUPPORTED;
@@ -76,7 +76,7 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
 {
     int rc = tile_valid(dm, t);
     if (rc != PS_OK) return rc;
-    const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.bpp);
+    const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.ring);
     ConvArgs a;
     a.in = in; a.wt = wt; a.out = out;
     a.H = dm.H; a.W = dm.W; a.Cb = dm.Cb; a.Kb = dm.Kb; a.R = dm.R; a.S = dm.S;

@@ -17,13 +17,24 @@
 //   * The reduction index inside one 16-channel block is permuted: at MFMA step t the lanes
 //     0..31 supply channel t and lanes 32..63 channel 8 + t.  A sum does not care, and it lets a
 //     lane fetch its 8 channels of a pixel with two 16-byte LDS reads.
-//   * LDS holds, per pipeline stage, G batch elements: the gathered pixels [G][MT][16 c (+4 pad)]
-//     and the filter rows [G][16 c][KT].  The 80-byte pixel pitch spreads 8 consecutive pixels
-//     over all 32 banks for the 16-byte reads.
-//   * Two LDS buffers: global loads of stage i+1 are issued into registers before the MFMAs of
-//     stage i and written to the other buffer after them; one barrier per stage.
-//   * Global loads are raw buffer loads: an out-of-image tap or an exhausted batch range gets an
-//     offset past the buffer size and reads as zero, with no branch.
+//   * LDS is a ring of NBUF slots, one batch element each: the gathered pixels [MT][16 c] and the
+//     filter blocks [KT/16][16 c][16 k].  Global memory is copied straight into LDS by buffer loads
+//     with the LDS modifier (no staging registers, no LDS store instructions).  Such a load places
+//     lane i's 16 bytes at base + 16*i, so the layout in LDS is decided by which global address each
+//     lane asks for: the four 16-byte chunks of a pixel are stored at position chunk ^ ((pixel>>1)&3),
+//     which spreads 8 consecutive pixels over all 32 banks for the 16-byte fragment reads, and each
+//     1 KB filter block gets a 64-byte pad so that the two blocks a 32-channel fragment spans do
+//     not share banks.
+//   * A load whose tap falls outside the image, whose pixel is past the end of the tensor or whose
+//     batch element is past the end of the range asks for an offset beyond the buffer size: the
+//     hardware returns zeros, so padding needs no branch and no separate fill.
+//   * Pipeline, per batch element b: wait for this wave's loads of element b+1, barrier (everyone's
+//     b+1 is in LDS, and everyone holds element b's fragments in registers, so slot b is free), issue
+//     the loads of element b+NBUF into slot b, read the fragments of b+1 into the other register set,
+//     run the MFMAs of b.  LDS reads, loads and address arithmetic interleave with the MFMAs of the
+//     same iteration; a load has NBUF-1 iterations to land.
+//   * The batch range is padded to a multiple of NBUF with all-zero elements (out-of-range loads),
+//     which keeps the unrolled loop free of guards.
 //   * Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id is remapped so
 //     that each XCD works on a contiguous run of tiles and neighbouring tiles share its L2.
 #pragma once
@@ -33,7 +44,7 @@ namespace ps {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 struct ConvArgs {
     const void *in;
@@ -88,33 +99,55 @@ __device__ inline TileCoord decode_tile(const ConvArgs &a)
     return tc;
 }
 
-template <int KT, int MT, int WK, int WM, int G>
+// s_waitcnt vmcnt(N) lgkmcnt(0), then s_barrier.  The wait is emitted through the builtin so that the
+// compiler's own wait-count bookkeeping sees it (it cannot look inside inline assembly and would
+// otherwise add redundant waits in front of the MFMAs).
+template <int N>
+__device__ inline void wait_vm_and_barrier()
+{
+    // gfx9 immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]; expcnt 7 = no wait
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int KT, int MT, int WK, int WM, int NBUF>
 struct F32Shape {
-    static constexpr int NT = 64 * WK * WM;
-    static constexpr int TK = KT / (WK * 32);
-    static constexpr int TM = MT / (WM * 32);
-    static constexpr int PIXP = 20;  // floats per staged pixel: 16 channels + 4 pad
-    static constexpr int A_ST = G * MT * PIXP;
-    static constexpr int W_ST = G * 16 * KT;
-    static constexpr int ST = A_ST + W_ST;
-    static constexpr int APT = MT * 4 / NT;  // 16-byte input chunks per thread per batch element
-    static constexpr int WPT = (KT * 4 + NT - 1) / NT;  // 16-byte filter chunks per thread per batch element
-    static constexpr int LDS_BYTES = 2 * ST * 4;
+    static constexpr int NW = WK * WM;
+    static constexpr int NT = 64 * NW;
+    static constexpr int TK = KT / (WK * 32);  // 32x32 MFMA tiles per wave, output-channel direction
+    static constexpr int TM = MT / (WM * 32);  // ... pixel direction
+    static constexpr int PGRP = MT / 16;       // 1 KB groups of 16 pixels per batch element
+    static constexpr int WBLK = KT / 16;       // 1 KB filter blocks per batch element
+    static constexpr int APW = (PGRP + NW - 1) / NW;
+    static constexpr int WPW = (WBLK + NW - 1) / NW;
+    static constexpr int LPE = APW + WPW;      // load instructions per wave per batch element (same for all waves)
+    static constexpr int WPITCH = 1024 + 64;   // bytes from one filter block to the next in LDS
+    static constexpr int A_BYTES = MT * 64;
+    static constexpr int W_BYTES = WBLK * WPITCH;
+    static constexpr int SLOT = A_BYTES + W_BYTES;
+    // waves with no real group/block left still issue their load (keeps vmcnt uniform) into a dump area
+    static constexpr bool DUMMY = (PGRP % NW != 0) || (WBLK % NW != 0);
+    static constexpr int LDS_BYTES = NBUF * SLOT + (DUMMY ? 1024 : 0);
+    static constexpr int D = NBUF;  // prefetch distance in batch elements
     static_assert(KT % (WK * 32) == 0 && MT % (WM * 32) == 0, "wave tile must be whole 32x32 MFMA tiles");
-    static_assert((MT * 4) % NT == 0, "loader needs whole pixel chunks per thread");
+    static_assert(NBUF >= 2 && NBUF % 2 == 0, "ring size must be even (fragment register parity)");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert((D - 2) * LPE <= 63, "vmcnt range");
 };
 
-template <int KT, int MT, int WK, int WM, int G>
+template <int KT, int MT, int WK, int WM, int NBUF>
 __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvArgs a)
 {
-    using Sh = F32Shape<KT, MT, WK, WM, G>;
-    constexpr int NT = Sh::NT, TK = Sh::TK, TM = Sh::TM, PIXP = Sh::PIXP;
-    constexpr int APT = Sh::APT, WPT = Sh::WPT;
-    __shared__ __attribute__((aligned(16))) float lds[2 * Sh::ST];
+    using Sh = F32Shape<KT, MT, WK, WM, NBUF>;
+    constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
+    constexpr int APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
+    __shared__ __attribute__((aligned(1024))) char lds[Sh::LDS_BYTES];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WK, wm = wave / WK;
     const int half = lane >> 5, l32 = lane & 31;
 
@@ -127,13 +160,16 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, a.wt_bytes);
 
-    // ---- per-thread gather bookkeeping: which pixels this thread stages ------------------
-    const int chunk = tid & 3;  // which 16 bytes of the pixel's 64
-    int poff[APT], h0[APT], w0[APT];
+    // ---- loader bookkeeping ---------------------------------------------------------------------
+    // One load instruction fills one 1 KB pixel group: lane -> pixel group*16 + lane/4, LDS chunk
+    // position lane%4, which holds global chunk (lane%4) ^ ((pixel >> 1) & 3) = (lane%4) ^ ((lane>>3)&3).
+    const int gchunk = (lane & 3) ^ ((lane >> 3) & 3);
+    int poff[APW], h0[APW], w0[APW];
 #pragma unroll
-    for (int i = 0; i < APT; ++i) {
-        const int m = m0 + (tid >> 2) + i * (NT / 4);
-        if (m < a.M) {
+    for (int i = 0; i < APW; ++i) {
+        const int grp = i * NW + wave;
+        const int m = m0 + grp * 16 + (lane >> 2);
+        if (grp < Sh::PGRP && m < a.M) {
             const int n = m / a.PQ;
             const int pq = m - n * a.PQ;
             const int p = pq / a.Q;
@@ -142,67 +178,80 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
             w0[i] = q * a.stride - a.pad;
             poff[i] = (n * a.Cb * a.H + h0[i]) * a.W + w0[i];
         } else {
-            h0[i] = -(1 << 24);  // never inside the image: the tail of the last tile reads zeros
+            h0[i] = -(1 << 24);
             w0[i] = 0;
             poff[i] = 0;
         }
     }
-
-    // position of the next batch element to load, kept as (cb, r, s) counters
     int lb = b_begin;
     int lcb = lb / (a.R * a.S);
     int lr = (lb - lcb * a.R * a.S) / a.S;
     int ls = lb - (lcb * a.R + lr) * a.S;
 
-    uintx4 areg[G][APT], wreg[G][WPT];
-
-    auto issue_loads = [&]() {
+    auto issue_loads = [&](int slot) {
+        const bool bv = lb < b_end;
+        const int tapoff = (lcb * a.H + lr) * a.W + ls;
+        char *sbase = lds + slot * Sh::SLOT;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const bool bv = lb < b_end;
-            const int tapoff = (lcb * a.H + lr) * a.W + ls;
-#pragma unroll
-            for (int i = 0; i < APT; ++i) {
-                const bool ok = bv && (unsigned)(h0[i] + lr) < (unsigned)a.H && (unsigned)(w0[i] + ls) < (unsigned)a.W;
-                const unsigned off = ok ? (unsigned)((poff[i] + tapoff) * 64 + chunk * 16) : kOobOffset;
-                areg[g][i] = __builtin_amdgcn_raw_buffer_load_b128(rin, off, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < WPT; ++i) {
-                const int id = tid + i * NT;
-                const bool wv = bv && (KT * 4 % NT == 0 || id < KT * 4) && kb0 + (id >> 6) < a.Kb;
-                const unsigned off = wv ? (unsigned)((((kb0 + (id >> 6)) * a.NB + lb) << 10) + ((id & 63) << 4)) : kOobOffset;
-                wreg[g][i] = __builtin_amdgcn_raw_buffer_load_b128(rwt, off, 0, 0);
-            }
-            ++lb;
-            if (++ls == a.S) {
-                ls = 0;
-                if (++lr == a.R) {
-                    lr = 0;
-                    ++lcb;
-                }
-            }
+        for (int i = 0; i < APW; ++i) {
+            const int grp = i * NW + wave;
+            const bool ok = bv & ((unsigned)(h0[i] + lr) < (unsigned)a.H) & ((unsigned)(w0[i] + ls) < (unsigned)a.W);
+            const unsigned off = ok ? (unsigned)((poff[i] + tapoff) * 64 + gchunk * 16) : kOobOffset;
+            char *dst = (Sh::PGRP % NW == 0 || grp < Sh::PGRP) ? sbase + grp * 1024 : lds + NBUF * Sh::SLOT;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rin, (lds_ptr_t)dst, 16, off, 0, 0, 0);
         }
+#pragma unroll
+        for (int i = 0; i < WPW; ++i) {
+            const int blk = i * NW + wave;
+            const bool wv = bv & (Sh::WBLK % NW == 0 || blk < Sh::WBLK) & (kb0 + blk < a.Kb);
+            const unsigned off = wv ? (unsigned)((((kb0 + blk) * a.NB + lb) << 10) + (lane << 4)) : kOobOffset;
+            char *dst = (Sh::WBLK % NW == 0 || blk < Sh::WBLK) ? sbase + Sh::A_BYTES + blk * Sh::WPITCH
+                                                               : lds + NBUF * Sh::SLOT;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr_t)dst, 16, off, 0, 0, 0);
+        }
+        ++lb;
+        // branch-free (r, s, c-block) odometer: keeps the whole iteration one basic block
+        ls += 1;
+        const int ws = ls == a.S;
+        ls = ws ? 0 : ls;
+        lr += ws;
+        const int wr = lr == a.R;
+        lr = wr ? 0 : lr;
+        lcb += wr;
     };
 
-    auto store_stage = [&](int buf) {
-        float *As = lds + buf * Sh::ST;
-        float *Ws = As + Sh::A_ST;
+    // ---- reader bookkeeping -------------------------------------------------------------
+    int paddr[TM], waddr[TK];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
+    for (int tm = 0; tm < TM; ++tm) {
+        const int p = (wm * TM + tm) * 32 + l32;
+        const int pos0 = (2 * half) ^ ((p >> 1) & 3);
+        paddr[tm] = p * 64 + pos0 * 16;
+    }
 #pragma unroll
-            for (int i = 0; i < APT; ++i) {
-                const int pix = (tid >> 2) + i * (NT / 4);
-                *reinterpret_cast<uintx4 *>(As + (g * MT + pix) * PIXP + chunk * 4) = areg[g][i];
-            }
+    for (int tk = 0; tk < TK; ++tk) {
+        const int ofm = (wk * TK + tk) * 32 + l32;
+        waddr[tk] = Sh::A_BYTES + (ofm >> 4) * Sh::WPITCH + half * 8 * 64 + (ofm & 15) * 4;
+    }
+
+    float pf[2][TM][8], wf[2][TK][8];
+    auto read_frags = [&](int slot, int par) {
+        const char *sbase = lds + slot * Sh::SLOT;
 #pragma unroll
-            for (int i = 0; i < WPT; ++i) {
-                const int id = tid + i * NT;
-                const int kbl = id >> 6, e = id & 63;
-                if (KT * 4 % NT != 0 && id >= KT * 4) continue;
-                *reinterpret_cast<uintx4 *>(Ws + (g * 16 + (e >> 2)) * KT + kbl * 16 + (e & 3) * 4) = wreg[g][i];
+        for (int tm = 0; tm < TM; ++tm) {
+            const floatx4 v0 = *reinterpret_cast<const floatx4 *>(sbase + paddr[tm]);
+            const floatx4 v1 = *reinterpret_cast<const floatx4 *>(sbase + (paddr[tm] ^ 16));
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                pf[par][tm][t] = v0[t];
+                pf[par][tm][4 + t] = v1[t];
             }
         }
+#pragma unroll
+        for (int tk = 0; tk < TK; ++tk)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                wf[par][tk][t] = *reinterpret_cast<const float *>(sbase + waddr[tk] + t * 64);
     };
 
     floatx16 acc[TK][TM];
@@ -213,52 +262,39 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tk][tm][r] = 0.f;
 
-    auto compute_stage = [&](int buf) {
-        const float *As = lds + buf * Sh::ST;
-        const float *Ws = As + Sh::A_ST;
+    auto mfmas = [&](int par) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float pf[TM][8], wf[TK][8];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const float *p = As + (g * MT + (wm * TM + tm) * 32 + l32) * PIXP + half * 8;
-                const floatx4 v0 = *reinterpret_cast<const floatx4 *>(p);
-                const floatx4 v1 = *reinterpret_cast<const floatx4 *>(p + 4);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    pf[tm][t] = v0[t];
-                    pf[tm][4 + t] = v1[t];
-                }
-            }
+        for (int t = 0; t < 8; ++t)
 #pragma unroll
             for (int tk = 0; tk < TK; ++tk)
 #pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    wf[tk][t] = Ws[(g * 16 + half * 8 + t) * KT + (wk * TK + tk) * 32 + l32];
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int tk = 0; tk < TK; ++tk)
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-                        acc[tk][tm] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[tk][t], pf[tm][t], acc[tk][tm], 0, 0, 0);
-        }
+                for (int tm = 0; tm < TM; ++tm)
+                    acc[tk][tm] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[par][tk][t], pf[par][tm][t], acc[tk][tm], 0, 0, 0);
     };
 
-    // ---- software pipeline over stages of G batch elements ------------------------------
-    const int nstage = (a.nb_split + G - 1) / G;
-    issue_loads();
-    store_stage(0);
-    __syncthreads();
-    for (int st = 0; st < nstage; ++st) {
-        const bool more = st + 1 < nstage;
-        if (more) issue_loads();
-        compute_stage(st & 1);
-        if (more) store_stage((st + 1) & 1);
-        __syncthreads();
-    }
+    // ---- pipeline ---------------------------------------------------------------------------
+    const int nb = a.nb_split;
+#pragma unroll
+    for (int e = 0; e < D; ++e) issue_loads(e);  // elements 0..D-1 (zero-filled beyond the range)
+    wait_vm_and_barrier<(D - 1) * LPE>();        // element 0 has landed everywhere
+    read_frags(0, 0);
 
-    // ---- epilogue: accumulators -> out[n][kb][p][q][16 k] --------------------------------
+    // iteration b: slot b % NBUF, fragment parity b % 2; unrolled by NBUF (even) so both are static.
+    // The range is padded up to a multiple of NBUF with zero elements (loads past b_end read zeros).
+    static_assert(NBUF % 2 == 0, "ring size must be even");
+    for (int b0 = 0; b0 < nb; b0 += NBUF) {
+#pragma unroll
+        for (int u = 0; u < NBUF; ++u) {
+            wait_vm_and_barrier<(D - 2) * LPE>();
+            read_frags((u + 1) % NBUF, (u + 1) % 2);
+            issue_loads(u % NBUF);
+            mfmas(u % 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ---- epilogue -------------------------------------------------------------------------------
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int m = m0 + (wm * TM + tm) * 32 + l32;
@@ -270,7 +306,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
-                if (ofm >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
+                if (ofm >= a.Kb * 16) continue;
                 float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
                 if (a.c_split == 1) {
                     floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
@@ -285,19 +321,21 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
     }
 }
 
+
 // One compiled kernel shape and how to launch it.
 struct ShapeEntry {
-    int dtype, kt, mt, bpp, threads, lds_bytes;
+    int dtype, kt, mt, ring, threads, lds_bytes;
     void (*launch)(const ConvArgs &, unsigned grid, hipStream_t);
 };
 
-template <int KT, int MT, int WK, int WM, int G>
+template <int KT, int MT, int WK, int WM, int NBUF>
 void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((conv_fwd_f32_kernel<KT, MT, WK, WM, G>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
+    hipLaunchKernelGGL((conv_fwd_f32_kernel<KT, MT, WK, WM, NBUF>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
 
-#define PS_F32_SHAPE(KT, MT, WK, WM, G)                                                               \
-    {PS_F32, KT, MT, G, 64 * WK * WM, F32Shape<KT, MT, WK, WM, G>::LDS_BYTES, &launch_f32<KT, MT, WK, WM, G>}
+#define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
+    {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES,                      \
+     &launch_f32<KT, MT, WK, WM, NBUF>}
 
 }  // namespace ps

@@ -32,9 +32,9 @@ int launch_conv_f32(const Dims &dm, const ps_tile &t, const float *in, const flo
                     hipStream_t stream);
 int launch_conv_bf16(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out,
                      hipStream_t stream);
-bool conv_shape_compiled(int dtype, int kt, int mt, int bpp);
-int conv_shape_lds_bytes(int dtype, int kt, int mt, int bpp);
-int conv_shape_threads(int dtype, int kt, int mt, int bpp);
+bool conv_shape_compiled(int dtype, int kt, int mt, int ring);
+int conv_shape_lds_bytes(int dtype, int kt, int mt, int ring);
+int conv_shape_threads(int dtype, int kt, int mt, int ring);
 int launch_fill_zero(float *p, size_t n, hipStream_t stream);
 
 }  // namespace ps

@@ -22,35 +22,39 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, bpp, threads, lds_bytes;
+    int kt, mt, ring, threads, lds_bytes;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
 
 namespace {
 
+// Per-chip constants (MI355X: 256 CUs in 8 XCDs).  Bandwidths are sustained figures measured with
+// streaming microbenchmarks on the device, not spec-sheet peaks.
 struct Chip {
     double cus = 256, xcds = 8;
     double clock_hz = 2.4e9;
     double lds_bytes = 160 * 1024;
+    double regs_per_simd = 512;               // VGPRs + AGPRs per lane
     double l2_bytes = 4.0 * 1024 * 1024;      // per XCD
     double mall_bytes = 256.0 * 1024 * 1024;  // Infinity Cache
-    double hbm_bw = 8.0e12 * 0.80;            // sustained fraction of 8 TB/s
-    double mall_bw = 14.0e12;
-    double l2_bw = 2048.0 * 8 * 2.4e9 * 0.5;  // 2 KB/clk/XCD peak, half sustained
-    double lds_bw_cu = 128.0;                 // bytes/clk/CU
-    double mfma_flop_clk_cu_f32 = 256.0;
-    double mfma_flop_clk_cu_bf16 = 4096.0;
-    double launch_us = 2.0;                   // grid launch + drain
-    double stage_latency_clk = 2500.0;        // first global->LDS fill of a workgroup
-    int max_waves_simd = 2;                   // register budget of these kernels
+    double hbm_bw = 5.0e12;                   // read+write streaming beyond the Infinity Cache
+    double mall_bw = 9.0e12;                  // working set resident in the Infinity Cache
+    double l2_bw = 14.0e12;                   // L2 -> LDS, all XCDs
+    double atomic_bw = 0.8e12;                // fp32 atomic adds, bytes of payload per second
+    double mfma_flop_clk_cu[2] = {256.0, 4096.0};  // f32, bf16
+    double steady_eff = 0.84;                 // matrix-core issue efficiency of the pipelined loop
+    double fill_clk = 6000.0;                 // first loads of a workgroup (nothing to overlap with)
+    double launch_us = 1.5;
 };
 
 const Chip kChip;
 
-struct Model {
-    double us;
-};
-
+// Working sets of the tile's data reuses, and the level each one is served from (the analogue of
+// Algorithms 1 and 2): accumulators -> registers, one batch element of pixels and filters -> LDS
+// (both by construction of the kernel), the filter slice and input slab shared by the workgroups of
+// one XCD -> that XCD's L2 if they fit, else the Infinity Cache, else HBM.  The cost is the time the
+// slowest level needs for the bytes it has to move (Eq. 1 with latency folded into per-workgroup
+// fill and launch terms), plus a fraction of the second-slowest for imperfect overlap.
 double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh)
 {
     const Chip &c = kChip;
@@ -58,66 +62,57 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh)
     const double n_mt = std::ceil(M / t.mt), n_kt = std::ceil((double)dm.K / t.kt);
     const double nwg = n_mt * n_kt * t.c_split;
     const double nb_split = (double)dm.NB / t.c_split;
-    const double nstage = std::ceil(nb_split / t.bpp);
+    const double nb_pad = std::ceil(nb_split / t.ring) * t.ring;  // zero elements pad the range
     const double es = dm.es;
-
-    // residency: workgroups per CU allowed by LDS and by the register budget
     const double waves_wg = sh.threads / 64.0;
+
+    // ---- residency --------------------------------------------------------------------------------
+    const double tiles_wave = (double)t.kt * t.mt / (waves_wg * 1024.0);  // 32x32 MFMA tiles per wave
+    const double regs = 16.0 * tiles_wave + 2.0 * 8.0 * 2.0 * std::sqrt(tiles_wave) + 48.0;
+    const double waves_simd = std::max(1.0, std::min(8.0, std::floor(c.regs_per_simd / regs)));
     double occ = std::floor(c.lds_bytes / sh.lds_bytes);
-    occ = std::min(occ, std::floor(c.max_waves_simd * 4.0 / waves_wg));
-    occ = std::max(occ, 1.0);
+    occ = std::max(1.0, std::min(occ, std::floor(waves_simd * 4.0 / waves_wg)));
 
-    // matrix-core time of one workgroup (staged work includes the ragged last stage)
-    const double flop_wg = 2.0 * t.mt * t.kt * 16.0 * nstage * t.bpp;
-    const double rate = dm.dtype == PS_F32 ? c.mfma_flop_clk_cu_f32 : c.mfma_flop_clk_cu_bf16;
-    // LDS bytes read per workgroup stage: every wave reads its pixel rows and its filter columns
-    const int wk = sh.kt >= 128 ? 2 : (sh.kt == 64 ? (sh.mt >= 256 ? 1 : 2) : 1);
-    const double wm = waves_wg / wk;
-    const double lds_rd = t.bpp * 16.0 * es * (t.mt * wk + t.kt * wm);
-    const double lds_wr = t.bpp * 16.0 * es * (t.mt + t.kt);
-    const double clk_mfma_stage = 2.0 * t.mt * t.kt * 16.0 * t.bpp / rate;
-    const double clk_lds_stage = (lds_rd + lds_wr) / c.lds_bw_cu;
-    // with one resident workgroup nothing overlaps the barrier and LDS phases
-    const double overlap = occ >= 2 ? 1.0 : 0.0;
-    const double clk_stage = overlap > 0 ? std::max(clk_mfma_stage, clk_lds_stage) + 0.05 * clk_mfma_stage
-                                         : clk_mfma_stage + clk_lds_stage + 200.0;
-    const double clk_wg = nstage * clk_stage;
-    const double clk_epi = t.mt * t.kt * 4.0 / 64.0 * (t.c_split > 1 ? 4.0 : 1.0) / waves_wg;  // store issue
-
-    // wave quantisation: CUs that get the most workgroups finish last
+    // ---- matrix cores -----------------------------------------------------------------------------
+    // a workgroup with fewer than 4 waves leaves SIMDs idle unless several are resident
+    const double simd_share = std::min(1.0, waves_wg * std::min(occ, std::ceil(nwg / c.cus)) / 4.0);
+    const double rate = c.mfma_flop_clk_cu[dm.dtype == PS_F32 ? 0 : 1] * c.steady_eff * simd_share;
+    const double clk_wg = 2.0 * t.mt * t.kt * 16.0 * nb_pad / rate;
+    const double clk_epi = t.mt * t.kt / 64.0 / waves_wg * (t.c_split > 1 ? 6.0 : 1.5);
+    // wave quantisation: the CUs that get the most workgroups finish last
     const double per_cu = std::ceil(nwg / c.cus);
-    const double fill = c.stage_latency_clk * (occ >= 2 ? std::ceil(per_cu / occ) * 0.5 : per_cu);
-    const double t_mfma = (per_cu * (clk_wg + clk_epi) + fill) / c.clock_hz;
-    (void)flop_wg;
+    const double rounds = std::ceil(per_cu / occ);
+    const double t_mfma = (per_cu * (clk_wg + clk_epi) + rounds * c.fill_clk) / c.clock_hz;
 
-    // bytes that cross each level
+    // ---- bytes that cross each level --------------------------------------------------------------
     const double in_bytes = (double)dm.N * dm.Cb * dm.H * dm.W * 16.0 * es;
-    const double wt_bytes = (double)dm.K * dm.Cb * 16.0 * dm.R * dm.S * es;
+    const double wt_bytes = (double)dm.Kb * 16.0 * dm.Cb * 16.0 * dm.R * dm.S * es;
     const double out_bytes = M * dm.K * 4.0;
-    // traffic into the CUs: every workgroup gathers its pixels once per batch element
-    const double cu_in = nwg * t.mt * 16.0 * es * nb_split;
-    const double cu_wt = nwg * t.kt * 16.0 * es * nb_split;
-    // working sets that decide where the re-reads are served from
-    //  - filter slice shared by the workgroups of one XCD
-    const double wt_ws = (t.raster == 0 ? wt_bytes : wt_bytes / n_kt);
-    //  - input slab one XCD's resident tiles touch
-    const double in_ws = in_bytes / c.xcds;
-    double l2_served = 0, mall_served = 0, hbm = in_bytes + wt_bytes + out_bytes * (t.c_split > 1 ? 2.0 : 1.0);
-    const double ws = wt_ws + in_ws;
-    if (ws <= c.l2_bytes) {
-        l2_served = cu_in + cu_wt;
-        hbm += wt_bytes * (c.xcds - 1);  // each XCD pulls the filters once
-    } else if (in_bytes + wt_bytes + out_bytes <= c.mall_bytes) {
-        l2_served = 0.5 * (cu_in + cu_wt);
-        mall_served = 0.5 * (cu_in + cu_wt);
-    } else {
-        mall_served = 0.5 * (cu_in + cu_wt);
-        hbm += 0.5 * (cu_in + cu_wt);
+    // into the CUs: every workgroup gathers its pixels and its filter slice once per batch element
+    const double cu_bytes = nwg * nb_pad * 16.0 * es * (t.mt + t.kt);
+    // what one XCD's resident workgroups touch between two uses of the same data
+    const double wg_xcd = std::min(nwg, c.cus * occ) / c.xcds;
+    double xcd_ws;
+    if (t.raster == 0)  // k tiles fastest: neighbours share pixels, all of them need every filter
+        xcd_ws = wt_bytes + in_bytes * std::min(1.0, wg_xcd / n_kt / n_mt);
+    else                // pixel tiles fastest: neighbours share one filter slice
+        xcd_ws = wt_bytes * std::min(1.0, std::ceil(wg_xcd / n_mt) / n_kt) + in_bytes * std::min(1.0, wg_xcd / n_mt);
+    const double total = in_bytes + wt_bytes + out_bytes;
+    double hbm = total + wt_bytes * (c.xcds - 1);  // compulsory: every XCD pulls the filters once
+    double beyond_l2 = hbm;
+    if (xcd_ws > c.l2_bytes) {
+        // re-reads miss L2: the operand that is not shared by neighbours is refetched per workgroup
+        const double refetch = (t.raster == 0 ? nwg * nb_pad * 16.0 * es * t.kt : nwg * nb_pad * 16.0 * es * t.mt);
+        beyond_l2 += refetch * std::min(1.0, (xcd_ws - c.l2_bytes) / xcd_ws);
     }
-    if (t.c_split > 1) mall_served += out_bytes * t.c_split;  // atomic traffic
-    const double t_mem = std::max({(l2_served + mall_served) / c.l2_bw, mall_served / c.mall_bw, hbm / c.hbm_bw});
-
-    return (std::max(t_mfma, t_mem) + 0.15 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us * (t.c_split > 1 ? 2 : 1);
+    const double far_bw = total <= 0.7 * c.mall_bytes ? c.mall_bw : c.hbm_bw;
+    double t_mem = std::max(cu_bytes / c.l2_bw, beyond_l2 / far_bw);
+    double t_extra = 0.0;
+    if (t.c_split > 1) {
+        t_mem += out_bytes * t.c_split / c.atomic_bw;   // atomic accumulation of partial tiles
+        t_extra = out_bytes / c.hbm_bw * 1e6 + c.launch_us;  // the clearing pass
+    }
+    return (std::max(t_mfma, t_mem) + 0.25 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us + t_extra;
 }
 
 struct Cand {
@@ -145,16 +140,16 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
             int shallowest = 1 << 30;
             for (int j = 0; j < ns; ++j)
                 if (shapes[j].kt == s.kt && shapes[j].mt == s.mt) {
-                    if (shapes[j].bpp <= nbs && nbs % shapes[j].bpp == 0) any_exact = true;
-                    shallowest = std::min(shallowest, shapes[j].bpp);
+                    if (shapes[j].ring <= nbs && nbs % shapes[j].ring == 0) any_exact = true;
+                    shallowest = std::min(shallowest, shapes[j].ring);
                 }
-            const bool exact = s.bpp <= nbs && nbs % s.bpp == 0;
-            if (any_exact ? !exact : s.bpp != shallowest) continue;
-            if (sp > 1 && base_wg * (sp / 2 > 0 ? sp / 2 : 1) >= 4 * 256) continue;  // split only under-filled grids
+            const bool exact = s.ring <= nbs && nbs % s.ring == 0;
+            if (any_exact ? !exact : s.ring != shallowest) continue;
+            if (sp > 1 && base_wg * sp > 8 * 256) continue;  // split only under-filled grids
             for (int raster = 0; raster < 2; ++raster) {
                 if (raster == 1 && (n_mt == 1 || dm.K <= s.kt)) continue;
                 Cand c;
-                c.t.kt = s.kt; c.t.mt = s.mt; c.t.bpp = s.bpp; c.t.c_split = sp; c.t.raster = raster;
+                c.t.kt = s.kt; c.t.mt = s.mt; c.t.ring = s.ring; c.t.c_split = sp; c.t.raster = raster;
                 c.sh = s;
                 out.push_back(c);
             }
@@ -197,7 +192,7 @@ extern "C" double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t)
     ShapeInfo shapes[128];
     const int ns = list_shapes(dm.dtype, shapes, 128);
     for (int i = 0; i < ns; ++i)
-        if (shapes[i].kt == t->kt && shapes[i].mt == t->mt && shapes[i].bpp == t->bpp)
+        if (shapes[i].kt == t->kt && shapes[i].mt == t->mt && shapes[i].ring == t->ring)
             return model_cost(dm, *t, shapes[i]);
     return -1.0;
 }
