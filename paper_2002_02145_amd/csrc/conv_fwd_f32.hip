@@ -4,19 +4,24 @@
 namespace ps {
 
 //               KT   MT  WK WM NBUF       wave tile (channels x pixels)
-#define PS_BOTH_RINGS(KT, MT, WK, WM) PS_F32_SHAPE(KT, MT, WK, WM, 2), PS_F32_SHAPE(KT, MT, WK, WM, 4)
+// Ring depths: a load has (NBUF - 1) iterations to land, and an iteration lasts 512 matrix-core cycles
+// per 32x32 tile a wave owns, so the small wave tiles get the deeper rings.
+#define PS_RINGS_24(KT, MT, WK, WM) PS_F32_SHAPE(KT, MT, WK, WM, 2), PS_F32_SHAPE(KT, MT, WK, WM, 4)
+#define PS_RINGS_48(KT, MT, WK, WM) PS_F32_SHAPE(KT, MT, WK, WM, 4), PS_F32_SHAPE(KT, MT, WK, WM, 8)
 static const ShapeEntry kF32Shapes[] = {
-    PS_BOTH_RINGS(256, 128, 4, 2),  // 64 x 64, 8 waves
-    PS_BOTH_RINGS(256, 64, 4, 1),   // 64 x 64
-    PS_BOTH_RINGS(128, 128, 2, 2),  // 64 x 64
-    PS_BOTH_RINGS(128, 64, 2, 2),   // 64 x 32
-    PS_BOTH_RINGS(128, 32, 4, 1),   // 32 x 32
-    PS_BOTH_RINGS(64, 256, 1, 4),   // 64 x 64
-    PS_BOTH_RINGS(64, 128, 2, 2),   // 32 x 64
-    PS_BOTH_RINGS(64, 64, 2, 2),    // 32 x 32
-    PS_BOTH_RINGS(64, 32, 2, 1),    // 32 x 32, 2 waves
-    PS_BOTH_RINGS(32, 128, 1, 4),   // 32 x 32
-    PS_BOTH_RINGS(32, 64, 1, 2),    // 32 x 32, 2 waves
+    PS_RINGS_24(256, 128, 4, 2),  // 64 x 64, 8 waves
+    PS_RINGS_24(256, 64, 4, 1),   // 64 x 64
+    PS_RINGS_24(128, 128, 2, 2),  // 64 x 64
+    PS_RINGS_24(64, 256, 1, 4),   // 64 x 64
+    PS_RINGS_24(128, 64, 2, 2),   // 64 x 32
+    PS_RINGS_24(64, 128, 2, 2),   // 32 x 64
+    PS_F32_SHAPE(128, 64, 2, 2, 8), PS_F32_SHAPE(64, 128, 2, 2, 8),
+    PS_F32_SHAPE(64, 64, 2, 2, 2),
+    PS_RINGS_48(64, 64, 2, 2),    // 32 x 32
+    PS_RINGS_48(128, 32, 4, 1),   // 32 x 32
+    PS_RINGS_48(32, 128, 1, 4),   // 32 x 32
+    PS_RINGS_48(64, 32, 2, 1),    // 32 x 32, 2 waves
+    PS_RINGS_48(32, 64, 1, 2),    // 32 x 32, 2 waves
 };
 
 const ShapeEntry *f32_shapes(int *count)

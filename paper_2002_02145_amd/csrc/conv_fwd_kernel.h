@@ -129,7 +129,10 @@ struct F32Shape {
     static constexpr int SLOT = A_BYTES + W_BYTES;
     // waves with no real group/block left still issue their load (keeps vmcnt uniform) into a dump area
     static constexpr bool DUMMY = (PGRP % NW != 0) || (WBLK % NW != 0);
-    static constexpr int LDS_BYTES = NBUF * SLOT + (DUMMY ? 1024 : 0);
+    static constexpr int EPITCH = 36;  // floats per pixel row of the epilogue patch: 32 channels + 4 pad
+    static constexpr int RING_BYTES = NBUF * SLOT + (DUMMY ? 1024 : 0);
+    static constexpr int EPI_BYTES = NW * 32 * EPITCH * 4;
+    static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
     static constexpr int D = NBUF;  // prefetch distance in batch elements
     static_assert(KT % (WK * 32) == 0 && MT % (WM * 32) == 0, "wave tile must be whole 32x32 MFMA tiles");
     static_assert(NBUF >= 2 && NBUF % 2 == 0, "ring size must be even (fragment register parity)");
@@ -294,33 +297,64 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // ---- epilogue -------------------------------------------------------------------------------
+    // ---- epilogue: accumulators -> out[n][kb][p][q][16 k] ---------------------------------------
+    if (a.c_split == 1) {
+        // A lane holds one pixel and 4 consecutive channels per register quad: one 16-byte store each.
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = m0 + (wm * TM + tm) * 32 + l32;
+            if (m >= a.M) continue;
+            const int n = m / a.PQ;
+            const int pq = m - n * a.PQ;
+#pragma unroll
+            for (int tk = 0; tk < TK; ++tk) {
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
+                    if (ofm >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
+                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
+                    const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
+                                       acc[tk][tm][rq * 4 + 3]};
+                    *reinterpret_cast<floatx4 *>(o) = v;
+                }
+            }
+        }
+        return;
+    }
+    // Split reduction: partial tiles are added into the cleared output with fp32 atomics.  Issued from
+    // the accumulator layout, one atomic instruction would touch 64 different 64-byte lines; each wave
+    // therefore turns its 32x32 tile around in a private LDS patch so that 16 consecutive lanes cover
+    // one pixel's 16-channel line and an instruction adds into 4 whole lines.
+    wait_vm_and_barrier<0>();  // zero-fill loads of the padded iterations may still be landing in the ring
+    float *stage = reinterpret_cast<float *>(lds) + wave * (32 * Sh::EPITCH);
+    const int rp = lane >> 3, c4 = lane & 7;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int m = m0 + (wm * TM + tm) * 32 + l32;
-        if (m >= a.M) continue;
-        const int n = m / a.PQ;
-        const int pq = m - n * a.PQ;
 #pragma unroll
         for (int tk = 0; tk < TK; ++tk) {
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
-                if (ofm >= a.Kb * 16) continue;
-                float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
-                if (a.c_split == 1) {
-                    floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
-                                 acc[tk][tm][rq * 4 + 3]};
-                    *reinterpret_cast<floatx4 *>(o) = v;
-                } else {
+                const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
+                                   acc[tk][tm][rq * 4 + 3]};
+                *reinterpret_cast<floatx4 *>(stage + l32 * Sh::EPITCH + rq * 8 + half * 4) = v;
+            }
+            const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + c4 * 4;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) atomicAdd(o + e, acc[tk][tm][rq * 4 + e]);
+            for (int i = 0; i < 4; ++i) {
+                const int pr = rp + 8 * i;
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + pr * Sh::EPITCH + c4 * 4);
+                const int m = m0 + (wm * TM + tm) * 32 + pr;
+                if (m < a.M && ofm < a.Kb * 16) {
+                    const int n = m / a.PQ;
+                    const int pq = m - n * a.PQ;
+                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) atomicAdd(o + e, v[e]);
                 }
             }
         }
     }
 }
-
 
 // One compiled kernel shape and how to launch it.
 struct ShapeEntry {

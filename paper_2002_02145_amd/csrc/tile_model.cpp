@@ -40,9 +40,10 @@ struct Chip {
     double hbm_bw = 5.0e12;                   // read+write streaming beyond the Infinity Cache
     double mall_bw = 9.0e12;                  // working set resident in the Infinity Cache
     double l2_bw = 14.0e12;                   // L2 -> LDS, all XCDs
-    double atomic_bw = 0.8e12;                // fp32 atomic adds, bytes of payload per second
+    double atomic_bw = 0.35e12;               // fp32 atomic adds (resolved memory-side across XCDs), payload bytes/s
     double mfma_flop_clk_cu[2] = {256.0, 4096.0};  // f32, bf16
     double steady_eff = 0.84;                 // matrix-core issue efficiency of the pipelined loop
+    double load_latency_clk = 1500.0;         // global load to LDS, L2 hit under load
     double fill_clk = 6000.0;                 // first loads of a workgroup (nothing to overlap with)
     double launch_us = 1.5;
 };
@@ -74,15 +75,22 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh)
     occ = std::max(1.0, std::min(occ, std::floor(waves_simd * 4.0 / waves_wg)));
 
     // ---- matrix cores -----------------------------------------------------------------------------
-    // a workgroup with fewer than 4 waves leaves SIMDs idle unless several are resident
-    const double simd_share = std::min(1.0, waves_wg * std::min(occ, std::ceil(nwg / c.cus)) / 4.0);
-    const double rate = c.mfma_flop_clk_cu[dm.dtype == PS_F32 ? 0 : 1] * c.steady_eff * simd_share;
-    const double clk_wg = 2.0 * t.mt * t.kt * 16.0 * nb_pad / rate;
-    const double clk_epi = t.mt * t.kt / 64.0 / waves_wg * (t.c_split > 1 ? 6.0 : 1.5);
-    // wave quantisation: the CUs that get the most workgroups finish last
+    // Work is quantised per SIMD: a CU gets ceil(nwg / CUs) workgroups, each SIMD of it a quarter of
+    // their waves, and a wave owns `tiles_wave` 32x32 accumulator tiles for the whole batch range.
     const double per_cu = std::ceil(nwg / c.cus);
+    const double per_simd = std::ceil(per_cu * waves_wg / 4.0);
+    const double mfma_clk = dm.dtype == PS_F32 ? 64.0 * 8.0 : 32.0;  // per 32x32 tile per batch element
+    const double clk_wave = tiles_wave * mfma_clk * nb_pad / c.steady_eff;
+    // per batch element a wave also pays a barrier and the issue of its loads and LDS reads; with a
+    // single resident wave per SIMD nothing hides that
+    const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
+    double clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * nb_pad;
+    // a load issued in iteration b must have landed (ring - 1) iterations later
+    const double clk_iter = tiles_wave * mfma_clk / c.steady_eff * waves_res;
+    clk_iter_overhead += std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) * nb_pad / waves_res;
+    const double clk_epi = tiles_wave * (t.c_split > 1 ? 900.0 : 250.0);
     const double rounds = std::ceil(per_cu / occ);
-    const double t_mfma = (per_cu * (clk_wg + clk_epi) + rounds * c.fill_clk) / c.clock_hz;
+    const double t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk) / c.clock_hz;
 
     // ---- bytes that cross each level --------------------------------------------------------------
     const double in_bytes = (double)dm.N * dm.Cb * dm.H * dm.W * 16.0 * es;
