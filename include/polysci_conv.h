@@ -19,7 +19,9 @@
  *
  * Layouts (B = 16, Cb = ceil(C/16), Kb = K/16; es = 4 bytes for PS_F32, 2 for PS_BF16)
  *   activations, blocked : [N][Cb][H][W][16 c]              element size es
- *   filters, blocked     : [Kb][Cb][R][S][16 c][16 k]       element size es   (k fastest)
+ *   filters, blocked     : [Kb][Cb][R][S][16 c][16 k]       PS_F32            (k fastest)
+ *                          [Kb][Cb][R][S][2][16 k][8 c]     PS_BF16: block entry (c, k) sits at [c/8][k][c%8],
+ *                                                           the reduction index packed for 16-bit MFMA operands
  *   outputs, blocked     : [N][Kb][P][Q][16 k]              always fp32
  *   plain tensors        : NCHW, KCRS, NKPQ, dense
  * Channel lanes c >= C of the blocked tensors hold +0.0.  K must be a multiple of 16.

@@ -12,6 +12,12 @@ Reading where the paper is silent: it only evaluates layers whose channel counts
 multiples of 16.  Here an input-channel count that is not a multiple of 16 is padded up with
 +0.0 lanes; output-channel counts must be multiples of 16.
 
+bf16 is not in the paper.  For 2-byte elements the 16x16 filter block is stored [c/8][16 k][8 c]
+instead of [16 c][16 k]: the same 256 values, permuted so that the 8 input channels a matrix-core
+lane multiplies are contiguous (the reduction index must be packed for 16-bit operands, the same
+idea as the channel-pair packing CPU libraries use for bf16).  Activations and outputs keep the
+order above.
+
 Every function is a pure permutation (plus zero fill) and keeps the dtype, so results can be
 compared bit for bit.
 """
@@ -66,6 +72,26 @@ def blocked_to_filt(blk: np.ndarray, C: int) -> np.ndarray:
         for kk in range(B):
             w[kk::B, c, :, :] = blk[:, c // B, :, :, c % B, kk]
     return w
+
+
+def filt_to_blocked_packed8(w: np.ndarray) -> np.ndarray:
+    """[K][C][R][S] -> [K/16][ceil(C/16)][R][S][2 (c/8)][16 k][8 (c%8)]: the 2-byte-element filter layout."""
+    std = filt_to_blocked(w)                                   # [Kb][Cb][R][S][16 c][16 k]
+    Kb, Cb, R, S = std.shape[:4]
+    out = np.zeros((Kb, Cb, R, S, 2, B, 8), dtype=w.dtype)
+    for c in range(B):
+        for k in range(B):
+            out[:, :, :, :, c // 8, k, c % 8] = std[:, :, :, :, c, k]
+    return out
+
+
+def blocked_packed8_to_filt(blk: np.ndarray, C: int) -> np.ndarray:
+    Kb, Cb, R, S = blk.shape[:4]
+    std = np.zeros((Kb, Cb, R, S, B, B), dtype=blk.dtype)
+    for c in range(B):
+        for k in range(B):
+            std[:, :, :, :, c, k] = blk[:, :, :, :, c // 8, k, c % 8]
+    return blocked_to_filt(std, C)
 
 
 def out_to_blocked(y: np.ndarray) -> np.ndarray:

@@ -1,12 +1,222 @@
-// bf16-input kernel shapes of the batch-reduce-GEMM convolution (fp32 accumulate and output).
+// bf16-input batch-reduce-GEMM convolution (fp32 accumulate and output) and its kernel shapes.
+//
+// Same decomposition as the fp32 kernel (see conv_fwd_kernel.h): output tile of MT flattened pixels x KT
+// output channels, batch-reduce over (c-block, r, s), LDS ring fed by buffer loads with LDS destination,
+// zero fill through out-of-range offsets, fragment double-buffering, guard-free padded loop.  What differs:
+//   * v_mfma_f32_32x32x16_bf16: one instruction covers a whole 16-channel block for a 32x32 tile, and a
+//     lane supplies 8 consecutive reduction elements (channels 8*(lane/32) .. +7) of its row/column.
+//   * A pixel's block is 32 bytes, so a lane's operand is one 16-byte LDS read at pixel*32 + (lane/32)*16;
+//     the 64 lanes of a read cover 1 KB contiguously: no swizzle needed.
+//   * Filter blocks use the [c/8][16 k][8 c] order: a lane's operand is the 16 bytes at
+//     block*512 + (lane/32)*256 + (k%16)*16, again contiguous across lanes.
+//   * A batch element is only 32 matrix-core cycles per 32x32 tile, so an iteration (one barrier) handles
+//     G batch elements and a ring slot holds G elements.
 #include "conv_fwd_kernel.h"
 
 namespace ps {
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int KT, int MT, int WK, int WM, int NBUF, int G>
+struct Bf16Shape {
+    static constexpr int NW = WK * WM;
+    static constexpr int TK = KT / (WK * 32);
+    static constexpr int TM = MT / (WM * 32);
+    static constexpr int PGRP = MT / 32;  // 1 KB groups of 32 pixels per batch element
+    static constexpr int WINS = KT / 32;  // 1 KB pairs of filter blocks per batch element
+    static constexpr int APW = (PGRP + NW - 1) / NW;
+    static constexpr int WPW = (WINS + NW - 1) / NW;
+    static constexpr int LPS = G * (APW + WPW);  // load instructions per wave per ring slot
+    static constexpr int A_EL = MT * 32;
+    static constexpr int W_EL = KT * 32;
+    static constexpr int SLOT = G * (A_EL + W_EL);
+    static constexpr bool DUMMY = (PGRP % NW != 0) || (WINS % NW != 0);
+    static constexpr int EPITCH = 36;
+    static constexpr int RING_BYTES = NBUF * SLOT + (DUMMY ? 1024 : 0);
+    static constexpr int EPI_BYTES = NW * 32 * EPITCH * 4;
+    static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+    static constexpr int D = NBUF;
+    static_assert(KT % (WK * 32) == 0 && MT % (WM * 32) == 0, "wave tile must be whole 32x32 MFMA tiles");
+    static_assert(NBUF >= 2 && NBUF % 2 == 0, "ring size must be even (fragment register parity)");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert((D - 2) * LPS <= 63, "vmcnt range");
+};
+
+template <int KT, int MT, int WK, int WM, int NBUF, int G>
+__global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvArgs a)
+{
+    using Sh = Bf16Shape<KT, MT, WK, WM, NBUF, G>;
+    constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
+    constexpr int APW = Sh::APW, WPW = Sh::WPW, LPS = Sh::LPS, D = Sh::D;
+    __shared__ __attribute__((aligned(1024))) char lds[Sh::LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wk = wave % WK, wm = wave / WK;
+    const int half = lane >> 5, l32 = lane & 31;
+
+    const TileCoord tc = decode_tile(a);
+    const int m0 = tc.mtile * MT;
+    const int kb0 = tc.ktile * (KT / 16);
+    const int b_begin = tc.split * a.nb_split;
+    const int b_end = b_begin + a.nb_split;
+
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
+    const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, a.wt_bytes);
+
+    // ---- loader bookkeeping: one load fills 32 pixels (lane -> pixel lane/2, 16-byte half lane%2) ----
+    int poff[APW], h0[APW], w0[APW];
+#pragma unroll
+    for (int i = 0; i < APW; ++i) {
+        const int grp = i * NW + wave;
+        const int m = m0 + grp * 32 + (lane >> 1);
+        if (grp < Sh::PGRP && m < a.M) {
+            const int n = m / a.PQ;
+            const int pq = m - n * a.PQ;
+            const int p = pq / a.Q;
+            const int q = pq - p * a.Q;
+            h0[i] = p * a.stride - a.pad;
+            w0[i] = q * a.stride - a.pad;
+            poff[i] = (n * a.Cb * a.H + h0[i]) * a.W + w0[i];
+        } else {
+            h0[i] = -(1 << 24);
+            w0[i] = 0;
+            poff[i] = 0;
+        }
+    }
+    int lb = b_begin;
+    int lcb = lb / (a.R * a.S);
+    int lr = (lb - lcb * a.R * a.S) / a.S;
+    int ls = lb - (lcb * a.R + lr) * a.S;
+
+    auto issue_loads = [&](int slot) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const bool bv = lb < b_end;
+            const int tapoff = (lcb * a.H + lr) * a.W + ls;
+            char *abase = lds + slot * Sh::SLOT + g * Sh::A_EL;
+            char *wbase = lds + slot * Sh::SLOT + G * Sh::A_EL + g * Sh::W_EL;
+#pragma unroll
+            for (int i = 0; i < APW; ++i) {
+                const int grp = i * NW + wave;
+                const bool ok = bv & ((unsigned)(h0[i] + lr) < (unsigned)a.H) & ((unsigned)(w0[i] + ls) < (unsigned)a.W);
+                const unsigned off = ok ? (unsigned)((poff[i] + tapoff) * 32 + (lane & 1) * 16) : kOobOffset;
+                char *dst = (Sh::PGRP % NW == 0 || grp < Sh::PGRP) ? abase + grp * 1024 : lds + NBUF * Sh::SLOT;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rin, (lds_ptr_t)dst, 16, off, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < WPW; ++i) {
+                const int pair = i * NW + wave;           // filter blocks 2*pair and 2*pair + 1
+                const int kb = kb0 + 2 * pair + half;
+                const bool wv = bv & (Sh::WINS % NW == 0 || pair < Sh::WINS) & (kb < a.Kb);
+                const unsigned off = wv ? (unsigned)(((kb * a.NB + lb) << 9) + (l32 << 4)) : kOobOffset;
+                char *dst = (Sh::WINS % NW == 0 || pair < Sh::WINS) ? wbase + pair * 1024 : lds + NBUF * Sh::SLOT;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt, (lds_ptr_t)dst, 16, off, 0, 0, 0);
+            }
+            ++lb;
+            ls += 1;
+            const int ws = ls == a.S;
+            ls = ws ? 0 : ls;
+            lr += ws;
+            const int wr = lr == a.R;
+            lr = wr ? 0 : lr;
+            lcb += wr;
+        }
+    };
+
+    // ---- reader bookkeeping -------------------------------------------------------------------
+    int paddr[TM], waddr[TK];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) paddr[tm] = ((wm * TM + tm) * 32 + l32) * 32 + half * 16;
+#pragma unroll
+    for (int tk = 0; tk < TK; ++tk) {
+        const int ofm = (wk * TK + tk) * 32 + l32;
+        waddr[tk] = G * Sh::A_EL + (ofm >> 4) * 512 + half * 256 + (ofm & 15) * 16;
+    }
+
+    bf16x8 pf[2][G][TM], wf[2][G][TK];
+    auto read_frags = [&](int slot, int par) {
+        const char *sbase = lds + slot * Sh::SLOT;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                pf[par][g][tm] = *reinterpret_cast<const bf16x8 *>(sbase + g * Sh::A_EL + paddr[tm]);
+#pragma unroll
+            for (int tk = 0; tk < TK; ++tk)
+                wf[par][g][tk] = *reinterpret_cast<const bf16x8 *>(sbase + g * Sh::W_EL + waddr[tk]);
+        }
+    };
+
+    floatx16 acc[TK][TM];
+#pragma unroll
+    for (int tk = 0; tk < TK; ++tk)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tk][tm][r] = 0.f;
+
+    auto mfmas = [&](int par) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int tk = 0; tk < TK; ++tk)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    acc[tk][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[par][g][tk], pf[par][g][tm], acc[tk][tm], 0, 0, 0);
+    };
+
+    // ---- pipeline over ring slots of G batch elements (range padded with zero elements) -----------
+    const int nslot = (a.nb_split + G - 1) / G;
+#pragma unroll
+    for (int e = 0; e < D; ++e) issue_loads(e);
+    wait_vm_and_barrier<(D - 1) * LPS>();
+    read_frags(0, 0);
+    for (int s0 = 0; s0 < nslot; s0 += NBUF) {
+#pragma unroll
+        for (int u = 0; u < NBUF; ++u) {
+            wait_vm_and_barrier<(D - 2) * LPS>();
+            read_frags((u + 1) % NBUF, (u + 1) % 2);
+            issue_loads(u % NBUF);
+            mfmas(u % 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    write_out<KT, TK, TM, WK, Sh::EPITCH>(a, tc, acc, lds, m0, wave, lane);
+}
+
+template <int KT, int MT, int WK, int WM, int NBUF, int G>
+void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((conv_fwd_bf16_kernel<KT, MT, WK, WM, NBUF, G>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
+}
+
+#define PS_BF16_SHAPE(KT, MT, WK, WM, NBUF, G)                                                          \
+    {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES,                 \
+     &launch_bf16<KT, MT, WK, WM, NBUF, G>}
+#define PS_BF16_RINGS(KT, MT, WK, WM, G) PS_BF16_SHAPE(KT, MT, WK, WM, 2, G), PS_BF16_SHAPE(KT, MT, WK, WM, 4, G)
+
+//                 KT   MT  WK WM  G        wave tile (channels x pixels)
+static const ShapeEntry kBf16Shapes[] = {
+    PS_BF16_RINGS(256, 128, 4, 2, 2),  // 64 x 64, 8 waves
+    PS_BF16_RINGS(128, 128, 2, 2, 2),  // 64 x 64
+    PS_BF16_RINGS(64, 256, 1, 4, 2),   // 64 x 64
+    PS_BF16_RINGS(128, 64, 2, 2, 4),   // 64 x 32
+    PS_BF16_RINGS(64, 128, 2, 2, 4),   // 32 x 64
+    PS_BF16_RINGS(64, 64, 2, 2, 4),    // 32 x 32
+    PS_BF16_RINGS(32, 128, 1, 4, 4),   // 32 x 32
+    PS_BF16_RINGS(128, 32, 4, 1, 4),   // 32 x 32
+    PS_BF16_RINGS(64, 32, 2, 1, 4),    // 32 x 32, 2 waves
+    PS_BF16_RINGS(32, 64, 1, 2, 4),    // 32 x 32, 2 waves
+};
+
 const ShapeEntry *bf16_shapes(int *count)
 {
-    *count = 0;
-    return nullptr;
+    *count = (int)(sizeof(kBf16Shapes) / sizeof(kBf16Shapes[0]));
+    return kBf16Shapes;
 }
 
 }  // namespace ps

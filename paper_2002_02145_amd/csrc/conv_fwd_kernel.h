@@ -112,6 +112,73 @@ __device__ inline void wait_vm_and_barrier()
     asm volatile("" ::: "memory");
 }
 
+// Epilogue shared by the fp32 and bf16 kernels: accumulators -> out[n][kb][p][q][16 k].
+// acc[tk][tm] is the 32x32 tile (output channels x pixels) number (tk, tm) of this wave in the MFMA
+// result layout: register r of lane l holds channel 8*(r/4) + 4*(l/32) + r%4 of pixel l%32.
+template <int KT, int TK, int TM, int WK, int EPITCH>
+__device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx16 (&acc)[TK][TM], char *lds, int m0,
+                                 int wave, int lane)
+{
+    const int wk = wave % WK, wm = wave / WK;
+    const int half = lane >> 5, l32 = lane & 31;
+    if (a.c_split == 1) {
+        // A lane holds one pixel and 4 consecutive channels per register quad: one 16-byte store each.
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = m0 + (wm * TM + tm) * 32 + l32;
+            if (m >= a.M) continue;
+            const int n = m / a.PQ;
+            const int pq = m - n * a.PQ;
+#pragma unroll
+            for (int tk = 0; tk < TK; ++tk) {
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
+                    if (ofm >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
+                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
+                    const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
+                                       acc[tk][tm][rq * 4 + 3]};
+                    *reinterpret_cast<floatx4 *>(o) = v;
+                }
+            }
+        }
+        return;
+    }
+    // Split reduction: partial tiles are added into the cleared output with fp32 atomics.  Issued from
+    // the accumulator layout, one atomic instruction would touch 64 different 64-byte lines; each wave
+    // therefore turns its 32x32 tile around in a private LDS patch so that 16 consecutive lanes cover
+    // one pixel's 16-channel line and an instruction adds into 4 whole lines.
+    wait_vm_and_barrier<0>();  // zero-fill loads of the padded iterations may still be landing in the ring
+    float *stage = reinterpret_cast<float *>(lds) + wave * (32 * EPITCH);
+    const int rp = lane >> 3, c4 = lane & 7;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+        for (int tk = 0; tk < TK; ++tk) {
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
+                                   acc[tk][tm][rq * 4 + 3]};
+                *reinterpret_cast<floatx4 *>(stage + l32 * EPITCH + rq * 8 + half * 4) = v;
+            }
+            const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + c4 * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int pr = rp + 8 * i;
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + pr * EPITCH + c4 * 4);
+                const int m = m0 + (wm * TM + tm) * 32 + pr;
+                if (m < a.M && ofm < a.Kb * 16) {
+                    const int n = m / a.PQ;
+                    const int pq = m - n * a.PQ;
+                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) atomicAdd(o + e, v[e]);
+                }
+            }
+        }
+    }
+}
+
 template <int KT, int MT, int WK, int WM, int NBUF>
 struct F32Shape {
     static constexpr int NW = WK * WM;
@@ -297,63 +364,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // ---- epilogue: accumulators -> out[n][kb][p][q][16 k] ---------------------------------------
-    if (a.c_split == 1) {
-        // A lane holds one pixel and 4 consecutive channels per register quad: one 16-byte store each.
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int m = m0 + (wm * TM + tm) * 32 + l32;
-            if (m >= a.M) continue;
-            const int n = m / a.PQ;
-            const int pq = m - n * a.PQ;
-#pragma unroll
-            for (int tk = 0; tk < TK; ++tk) {
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
-                    if (ofm >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
-                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
-                    const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
-                                       acc[tk][tm][rq * 4 + 3]};
-                    *reinterpret_cast<floatx4 *>(o) = v;
-                }
-            }
-        }
-        return;
-    }
-    // Split reduction: partial tiles are added into the cleared output with fp32 atomics.  Issued from
-    // the accumulator layout, one atomic instruction would touch 64 different 64-byte lines; each wave
-    // therefore turns its 32x32 tile around in a private LDS patch so that 16 consecutive lanes cover
-    // one pixel's 16-channel line and an instruction adds into 4 whole lines.
-    wait_vm_and_barrier<0>();  // zero-fill loads of the padded iterations may still be landing in the ring
-    float *stage = reinterpret_cast<float *>(lds) + wave * (32 * Sh::EPITCH);
-    const int rp = lane >> 3, c4 = lane & 7;
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-        for (int tk = 0; tk < TK; ++tk) {
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
-                                   acc[tk][tm][rq * 4 + 3]};
-                *reinterpret_cast<floatx4 *>(stage + l32 * Sh::EPITCH + rq * 8 + half * 4) = v;
-            }
-            const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + c4 * 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int pr = rp + 8 * i;
-                const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + pr * Sh::EPITCH + c4 * 4);
-                const int m = m0 + (wm * TM + tm) * 32 + pr;
-                if (m < a.M && ofm < a.Kb * 16) {
-                    const int n = m / a.PQ;
-                    const int pq = m - n * a.PQ;
-                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) atomicAdd(o + e, v[e]);
-                }
-            }
-        }
-    }
+    write_out<KT, TK, TM, WK, Sh::EPITCH>(a, tc, acc, lds, m0, wave, lane);
 }
 
 // One compiled kernel shape and how to launch it.

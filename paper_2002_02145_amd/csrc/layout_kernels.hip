@@ -70,14 +70,17 @@ __global__ __launch_bounds__(kPix) void blocked_to_act_kernel(const T *__restric
 
 // plain [k][c][rs] <-> blocked [kb][cb][rs][16 c][16 k]; one thread per blocked element.
 // Filters are at most a few MB and transformed once per layer, so this stays a plain gather.
-template <typename T, bool kToBlocked>
+// With kPacked8 (2-byte elements) the block is [c/8][16 k][8 c]: the 8 input channels one bf16 MFMA
+// lane consumes are contiguous.
+template <typename T, bool kToBlocked, bool kPacked8>
 __global__ __launch_bounds__(256) void filt_kernel(const T *__restrict__ src, T *__restrict__ dst, int C,
                                                    int Cb, int RS, size_t nblk)
 {
     const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= nblk) return;
-    const int kk = e % kBlock;
-    const int cc = (e / kBlock) % kBlock;
+    const int in_blk = (int)(e % (kBlock * kBlock));
+    const int kk = kPacked8 ? (in_blk >> 3) & 15 : in_blk & 15;
+    const int cc = kPacked8 ? (in_blk >> 7) * 8 + (in_blk & 7) : in_blk >> 4;
     size_t rest = e / (kBlock * kBlock);
     const int rs = rest % RS;
     rest /= RS;
@@ -112,11 +115,11 @@ int run_filt(bool to_blocked, const void *src, void *dst, const Dims &dm, hipStr
     const size_t nblk = (size_t)dm.Kb * dm.Cb * dm.R * dm.S * kBlock * kBlock;
     const unsigned grid = (unsigned)((nblk + 255) / 256);
     if (to_blocked)
-        hipLaunchKernelGGL((filt_kernel<T, true>), dim3(grid), dim3(256), 0, st, (const T *)src, (T *)dst, dm.C,
-                           dm.Cb, dm.R * dm.S, nblk);
+        hipLaunchKernelGGL((filt_kernel<T, true, sizeof(T) == 2>), dim3(grid), dim3(256), 0, st, (const T *)src,
+                           (T *)dst, dm.C, dm.Cb, dm.R * dm.S, nblk);
     else
-        hipLaunchKernelGGL((filt_kernel<T, false>), dim3(grid), dim3(256), 0, st, (const T *)src, (T *)dst, dm.C,
-                           dm.Cb, dm.R * dm.S, nblk);
+        hipLaunchKernelGGL((filt_kernel<T, false, sizeof(T) == 2>), dim3(grid), dim3(256), 0, st, (const T *)src,
+                           (T *)dst, dm.C, dm.Cb, dm.R * dm.S, nblk);
     return hip_status(hipGetLastError());
 }
 

@@ -71,8 +71,9 @@ def test_descriptor_validation(ps):
 
 def test_tile_enumerator_and_model(ps):
     from shapes import EDGE_SHAPES
-    for shape in wl.resnet50_layers() + [wl.CFG1, wl.CFG3B] + EDGE_SHAPES:
-        d = ps.ConvDesc.of(shape)
+    for shape, dtype in [(s, t) for s in wl.resnet50_layers() + [wl.CFG1, wl.CFG3B] + EDGE_SHAPES
+                         for t in (ps.PS_F32, ps.PS_BF16)]:
+        d = ps.ConvDesc.of(shape, dtype)
         n = ps.ps_tile_count(d)
         assert n > 0
         tiles = [ps.ps_tile_get(d, i) for i in range(n)]
@@ -87,7 +88,7 @@ def test_tile_enumerator_and_model(ps):
         assert us == pytest.approx(min(costs))
         assert best.as_tuple() in {t.as_tuple() for t in tiles}
         # no variant can be modelled faster than the matrix cores allow
-        assert us * 1e-6 >= shape.flops_issued / 157.3e12 * 0.999
+        assert us * 1e-6 >= shape.flops_issued / (157.3e12 if dtype == ps.PS_F32 else 2.5e15) * 0.999
         with pytest.raises(ps.PsError):
             ps.ps_tile_get(d, n)
     assert not ps.ps_tile_valid(ps.ConvDesc.of(wl.CFG1), ps.Tile(128, 128, 2, 1, 0))   # K = 64 < kt

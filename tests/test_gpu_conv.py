@@ -22,12 +22,7 @@ def _prep(shape, gen, seed, dtype):
 
 
 def _dtypes():
-    from paper_2002_02145_amd import binding as ps
-    out = [0]
-    d = ps.ConvDesc.of(wl.CFG1, ps.PS_BF16)
-    if ps.lib.ps_tile_count(d) > 0:
-        out.append(1)
-    return out
+    return [0, 1]
 
 
 from shapes import EDGE_SHAPES
@@ -105,20 +100,23 @@ def test_full_size_configs_fp32(shape, seed):
         assert abs(got[n, k, p, q] - o) <= 1e-4 * m
 
 
-def test_resnet50_sweep_fp32():
+@pytest.mark.parametrize("dtype", [0, 1], ids=["fp32", "bf16"])
+def test_resnet50_sweep(dtype):
+    """Every layer of the ResNet-50-shaped sweep at N = 28 with the model's pick: one whole image plus
+    random samples of the rest.  bf16: inputs and filters rounded to bf16 first, oracle on the same values."""
     from gpu_util import run_conv
     for i, shape in enumerate(wl.resnet50_layers()):
-        x, w = wl.relu_like(shape, wl.sweep_seed(i))
-        got = run_conv(shape, x, w)
+        x, w = _prep(shape, wl.relu_like, wl.sweep_seed(i), dtype)
+        got = run_conv(shape, x, w, dtype)
         n = i % shape.N
         out, mag = oracle.conv2d_fwd(shape, x, w, images=(n, n + 1))
         err = oracle.normalised_error(got[n:n + 1], out[n:n + 1], mag[n:n + 1])
-        assert err <= 1e-4, f"{shape.name}: {err}"
+        assert err <= TOL[dtype], f"{shape.name}: {err}"
         rng = np.random.default_rng(i)
         for _ in range(100):
             nn, k, p, q = (int(rng.integers(v)) for v in (shape.N, shape.K, shape.P, shape.Q))
             o, m = oracle.conv2d_fwd_point(shape, x, w, nn, k, p, q)
-            assert abs(got[nn, k, p, q] - o) <= 1e-4 * m, shape.name
+            assert abs(got[nn, k, p, q] - o) <= TOL[dtype] * m, shape.name
 
 
 def test_invalid_arguments_launch_nothing():

@@ -51,3 +51,19 @@ def test_bit_patterns_survive(capsys):
     x = np.resize(bits, (1, 6, 1, 2)).view(np.float32)
     back = layout.blocked_to_act(layout.act_to_blocked(x), 6)
     np.testing.assert_array_equal(back.view(np.uint32), x.view(np.uint32))
+
+
+def test_packed8_filter_layout_is_a_permutation_of_the_standard_one():
+    K, C, R, S = 32, 20, 3, 2
+    w = np.arange(K * C * R * S, dtype=np.uint16).reshape(K, C, R, S)
+    std = layout.filt_to_blocked(w)
+    p8 = layout.filt_to_blocked_packed8(w)
+    assert p8.shape == (2, 2, R, S, 2, 16, 8)
+    flat = p8.ravel()
+    for k, c, r, s in [(0, 0, 0, 0), (31, 19, 2, 1), (16, 3, 1, 0), (15, 16, 0, 1), (17, 9, 2, 0), (5, 8, 1, 1)]:
+        cc, kk = c % 16, k % 16
+        off = ((((((k // 16) * 2 + c // 16) * R + r) * S + s) * 2 + cc // 8) * 16 + kk) * 8 + cc % 8
+        assert flat[off] == w[k, c, r, s]
+    # same multiset per block, zero lanes included
+    assert np.array_equal(np.sort(p8.reshape(2, 2, R, S, 256), -1), np.sort(std.reshape(2, 2, R, S, 256), -1))
+    np.testing.assert_array_equal(layout.blocked_packed8_to_filt(p8, C), w)
