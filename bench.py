@@ -111,11 +111,15 @@ def main(argv=None) -> int:
     y = torch.empty((shape.N, shape.K, shape.P, shape.Q), dtype=torch.float32, device=dev)
     ps.ps_nchw_to_blocked(d, xd, xb)
     ps.ps_kcrs_to_blocked(d, wd, wb)
-    tile, model_us = ps.ps_tile_select(d)
+    WS_CAP = 256 << 20   # workspace the caller is willing to lend for split reductions
+    tile, model_us = ps.ps_tile_select_ws(d, WS_CAP)
+    ws_bytes = ps.ps_workspace_bytes(d, tile)
+    ws = torch.empty(max(ws_bytes, 16) // 4, dtype=torch.float32, device=dev)
+    step = lambda: ps.ps_conv2d_fwd_ws(d, tile, xb, wb, ob, ws, ws_bytes)
 
-    wall_ms, ev_ms = _time_steps(lambda: ps.ps_conv2d_fwd(d, xb, wb, ob), a.steps, a.warmup)
+    wall_ms, ev_ms = _time_steps(step, a.steps, a.warmup)
     gflops = shape.flops / (wall_ms * 1e-3) * 1e-9
-    each_ms = _time_each(lambda: ps.ps_conv2d_fwd(d, xb, wb, ob), min(200, max(20, a.steps)))
+    each_ms = _time_each(step, min(200, max(20, a.steps)))
     kernel_tflops = shape.flops / (each_ms * 1e-3) * 1e-12
     from paper_2002_02145_amd.profile_summary import kernel_source_digest
     digest, tbytes = MEASURED_TRAFFIC.get(a.dtype, (None, None))
@@ -129,7 +133,7 @@ def main(argv=None) -> int:
             ("kcrs_to_blocked", lambda: ps.ps_kcrs_to_blocked(d, wd, wb), 2 * wb.numel() * es)):
         _, ms = _time_steps(fn, 50, 5)
         tr[name] = {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / (ms * 1e-3) * 1e-9, 1)}
-    _, e2e_ms = _time_steps(lambda: (ps.ps_nchw_to_blocked(d, xd, xb), ps.ps_conv2d_fwd(d, xb, wb, ob),
+    _, e2e_ms = _time_steps(lambda: (ps.ps_nchw_to_blocked(d, xd, xb), step(),
                                      ps.ps_blocked_to_nkpq(d, ob, y)), 50, 5)
 
     if a.ref_copy_mib > 0:
@@ -172,15 +176,17 @@ def main(argv=None) -> int:
             xi = torch.rand(ps.ps_blocked_in_bytes(dl) // es, device=dev, generator=g).to(tdt)
             wi = ((torch.rand(ps.ps_blocked_wt_bytes(dl) // es, device=dev, generator=g) - 0.5) * 0.1).to(tdt)
             oi = torch.empty(ps.ps_blocked_out_bytes(dl) // 4, device=dev, dtype=torch.float32)
-            t, _ = ps.ps_tile_select(dl)
+            t, _ = ps.ps_tile_select_ws(dl, WS_CAP)
+            wsb = ps.ps_workspace_bytes(dl, t)
+            wsl = torch.empty(max(wsb, 16) // 4, dtype=torch.float32, device=dev)
             reps = max(20, min(300, int(20e-3 / (L.flops_issued / (PEAK_TFLOPS[a.dtype] * 1e12 * 0.3)))))
-            _, ms = _time_steps(lambda: ps.ps_conv2d_fwd(dl, xi, wi, oi), reps, 5)
+            _, ms = _time_steps(lambda: ps.ps_conv2d_fwd_ws(dl, t, xi, wi, oi, wsl, wsb), reps, 5)
             tf = L.flops / (ms * 1e-3) * 1e-12
             layers.append({"layer": L.name, "us": round(ms * 1e3, 2), "TFLOP/s": round(tf, 2),
                            "frac_mfma_peak": round(tf / PEAK_TFLOPS[a.dtype], 4),
                            "frac_mfma_peak_issued": round(L.flops_issued / (ms * 1e-3) * 1e-12 / PEAK_TFLOPS[a.dtype], 4),
                            "tile": list(t.as_tuple())})
-            del xi, wi, oi
+            del xi, wi, oi, wsl
         tot_flop = sum(L.flops for L in wl.resnet50_layers())
         tot_s = sum(l["us"] for l in layers[:len(wl.resnet50_layers())]) * 1e-6
         agg = {"flop_weighted_TFLOP/s": round(tot_flop / tot_s * 1e-12, 2),

@@ -99,6 +99,16 @@ int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const void *wt_blk,
 int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const void *in_blk,
                        const void *wt_blk, void *out_blk, void *stream);
 
+/* Workspace variant for split reductions (c_split > 1): each split stores its partial tile into its own
+ * plane of `workspace` with plain stores and a second kernel adds the planes into out_blk; nothing is
+ * cleared and no atomics are used, so the result does not depend on arrival order.  `workspace` is a device
+ * buffer of at least ps_workspace_bytes(d, t) bytes, owned by the caller, 16-byte aligned, scratch (contents
+ * undefined afterwards); it may be NULL when the tile needs none.  t == NULL runs ps_tile_select_ws's pick
+ * for the given workspace size.  PS_EINVAL if the workspace is too small for the tile. */
+size_t ps_workspace_bytes(const ps_conv_desc *d, const ps_tile *t); /* c_split * N*K*P*Q*4, 0 if c_split == 1 */
+int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
+                     void *out_blk, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- outer-loop variant space and its ranking (Section 4.2, Algorithm 2, Eq. 1) ------- */
 /* Number of candidate tiles the enumerator emits for `d` (negative ps_status on error). */
 int ps_tile_count(const ps_conv_desc *d);
@@ -106,10 +116,15 @@ int ps_tile_count(const ps_conv_desc *d);
 int ps_tile_get(const ps_conv_desc *d, int idx, ps_tile *t);
 /* PS_OK if `t` can run `d` (a compiled kernel shape exists and the split divides evenly). */
 int ps_tile_valid(const ps_conv_desc *d, const ps_tile *t);
-/* Modelled execution time of `t` on `d` in microseconds; negative if invalid. */
+/* Modelled execution time of `t` on `d` in microseconds; negative if invalid.  ps_tile_cost_us prices a
+ * split reduction as ps_conv2d_fwd_tile runs it (clear + atomics), ps_tile_cost_ws_us as ps_conv2d_fwd_ws
+ * runs it (partial planes + reduction pass). */
 double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t);
+double ps_tile_cost_ws_us(const ps_conv_desc *d, const ps_tile *t);
 /* The candidate with the lowest modelled time (k = 1 of the paper's top-k pick). */
 int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us);
+/* Same for ps_conv2d_fwd_ws: only candidates whose workspace fits in `workspace_bytes` compete. */
+int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *best, double *modelled_us);
 
 const char *ps_strerror(int status);
 

@@ -33,13 +33,17 @@ def _buffers(desc: ps.ConvDesc, es: int, copies: int = 1):
 
 
 def time_tile(desc: ps.ConvDesc, tile: ps.Tile | None, sets, warmup: int = 5, min_ms: float = 20.0,
-              max_iters: int = 2000) -> float:
-    """Mean microseconds per launch of one tile (None = the library's own pick)."""
+              max_iters: int = 2000, workspace=None) -> float:
+    """Mean microseconds per launch of one tile (None = the library's own pick).  With a workspace tensor
+    the call goes through ps_conv2d_fwd_ws (split reductions use partial planes instead of atomics)."""
     stream = torch.cuda.current_stream()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
 
     def launch(i):
         xb, wb, ob = sets[i % len(sets)]
-        if tile is None:
+        if workspace is not None:
+            ps.ps_conv2d_fwd_ws(desc, tile, xb, wb, ob, workspace, ws_bytes, stream)
+        elif tile is None:
             ps.ps_conv2d_fwd(desc, xb, wb, ob, stream)
         else:
             ps.ps_conv2d_fwd_tile(desc, tile, xb, wb, ob, stream)
@@ -62,24 +66,31 @@ def time_tile(desc: ps.ConvDesc, tile: ps.Tile | None, sets, warmup: int = 5, mi
         iters = min(max_iters, max(iters * 2, int(iters * min_ms / max(ms, 1e-3)) + 1))
 
 
-def sweep(shape: wl.ConvShape, dtype: int = ps.PS_F32, min_ms: float = 20.0, cold: bool = False) -> dict:
+def sweep(shape: wl.ConvShape, dtype: int = ps.PS_F32, min_ms: float = 20.0, cold: bool = False,
+          use_ws: bool = True) -> dict:
     desc = ps.ConvDesc.of(shape, dtype)
     es = 4 if dtype == ps.PS_F32 else 2
     per_set = ps.ps_blocked_in_bytes(desc) + ps.ps_blocked_wt_bytes(desc) + ps.ps_blocked_out_bytes(desc)
     copies = max(1, -(-(600 << 20) // per_set)) if cold else 1
     sets = _buffers(desc, es, copies)
     rows = []
-    for i in range(ps.ps_tile_count(desc)):
-        t = ps.ps_tile_get(desc, i)
-        us = time_tile(desc, t, sets, min_ms=min_ms)
-        rows.append({"tile": t.as_tuple(), "us": us, "model_us": ps.ps_tile_cost_us(desc, t)})
-    pick, model_us = ps.ps_tile_select(desc)
+    tiles = [ps.ps_tile_get(desc, i) for i in range(ps.ps_tile_count(desc))]
+    workspace = None
+    if use_ws:
+        need = max([ps.ps_workspace_bytes(desc, t) for t in tiles] + [16])
+        workspace = torch.empty(need // 4, device="cuda", dtype=torch.float32)
+    cost = ps.ps_tile_cost_ws_us if use_ws else ps.ps_tile_cost_us
+    for t in tiles:
+        us = time_tile(desc, t, sets, min_ms=min_ms, workspace=workspace)
+        rows.append({"tile": t.as_tuple(), "us": us, "model_us": cost(desc, t)})
+    pick, model_us = ps.ps_tile_select_ws(desc, need) if use_ws else ps.ps_tile_select(desc)
     best = min(rows, key=lambda r: r["us"])
     worst = max(rows, key=lambda r: r["us"])
     mine = next(r for r in rows if r["tile"] == pick.as_tuple())
     gf = lambda us: shape.flops / us * 1e-3
     return {
         "layer": shape.name, "dtype": "f32" if dtype == ps.PS_F32 else "bf16", "candidates": len(rows),
+        "split_reduction": "workspace" if use_ws else "atomics",
         "pick": pick.as_tuple(), "pick_us": mine["us"], "pick_model_us": model_us, "pick_gflops": gf(mine["us"]),
         "best": best["tile"], "best_us": best["us"], "best_gflops": gf(best["us"]),
         "worst": worst["tile"], "worst_us": worst["us"], "worst_gflops": gf(worst["us"]),
@@ -96,6 +107,8 @@ def main(argv=None) -> int:
     ap.add_argument("--min-ms", type=float, default=20.0)
     ap.add_argument("--cold", action="store_true", help="rotate buffers so every launch streams from HBM")
     ap.add_argument("--rows", action="store_true", help="include every candidate's time in the output")
+    ap.add_argument("--atomics", action="store_true",
+                    help="time split reductions through ps_conv2d_fwd_tile (clear + atomics) instead of the workspace path")
     ap.add_argument("--out", default=None)
     a = ap.parse_args(argv)
     named = {"cfg1": wl.CFG1, "cfg2": wl.CFG2, "cfg3a": wl.CFG3A, "cfg3b": wl.CFG3B}
@@ -107,7 +120,7 @@ def main(argv=None) -> int:
     dtype = ps.PS_F32 if a.dtype == "f32" else ps.PS_BF16
     out = open(a.out, "w") if a.out else sys.stdout
     for shape in layers:
-        r = sweep(shape, dtype, a.min_ms, a.cold)
+        r = sweep(shape, dtype, a.min_ms, a.cold, use_ws=not a.atomics)
         if not a.rows:
             r.pop("rows")
         print(json.dumps(r), file=out, flush=True)

@@ -66,6 +66,10 @@ def _load() -> ctypes.CDLL:
         "ps_blocked_to_nkpq": (ctypes.c_int, [dp, vp, vp, vp]),
         "ps_conv2d_fwd": (ctypes.c_int, [dp, vp, vp, vp, vp]),
         "ps_conv2d_fwd_tile": (ctypes.c_int, [dp, tp, vp, vp, vp, vp]),
+        "ps_workspace_bytes": (ctypes.c_size_t, [dp, tp]),
+        "ps_conv2d_fwd_ws": (ctypes.c_int, [dp, tp, vp, vp, vp, vp, ctypes.c_size_t, vp]),
+        "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
+        "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_tile_count": (ctypes.c_int, [dp]),
         "ps_tile_get": (ctypes.c_int, [dp, ctypes.c_int, tp]),
         "ps_tile_valid": (ctypes.c_int, [dp, tp]),
@@ -147,6 +151,28 @@ def ps_conv2d_fwd(desc: ConvDesc, in_blk, wt_blk, out_blk, stream=None) -> None:
 def ps_conv2d_fwd_tile(desc: ConvDesc, tile: Tile, in_blk, wt_blk, out_blk, stream=None) -> None:
     _check(lib.ps_conv2d_fwd_tile(ctypes.byref(desc), ctypes.byref(tile), _ptr(in_blk), _ptr(wt_blk),
                                   _ptr(out_blk), _stream(stream)), "ps_conv2d_fwd_tile")
+
+
+def ps_workspace_bytes(desc: ConvDesc, tile: Tile) -> int:
+    return int(lib.ps_workspace_bytes(ctypes.byref(desc), ctypes.byref(tile)))
+
+
+def ps_conv2d_fwd_ws(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace, workspace_bytes: int, stream=None) -> None:
+    """tile=None lets the library pick among the tiles whose workspace fits."""
+    tp = ctypes.byref(tile) if tile is not None else None
+    _check(lib.ps_conv2d_fwd_ws(ctypes.byref(desc), tp, _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk),
+                                _ptr(workspace), int(workspace_bytes), _stream(stream)), "ps_conv2d_fwd_ws")
+
+
+def ps_tile_cost_ws_us(desc: ConvDesc, tile: Tile) -> float:
+    return float(lib.ps_tile_cost_ws_us(ctypes.byref(desc), ctypes.byref(tile)))
+
+
+def ps_tile_select_ws(desc: ConvDesc, workspace_bytes: int) -> tuple[Tile, float]:
+    t, us = Tile(), ctypes.c_double()
+    _check(lib.ps_tile_select_ws(ctypes.byref(desc), int(workspace_bytes), ctypes.byref(t), ctypes.byref(us)),
+           "ps_tile_select_ws")
+    return t, us.value
 
 
 def ps_tile_count(desc: ConvDesc) -> int:

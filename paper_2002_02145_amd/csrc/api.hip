@@ -72,7 +72,7 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     return PS_OK;
 }
 
-int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, hipStream_t st)
+int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, float *ws, hipStream_t st)
 {
     int rc = tile_valid(dm, t);
     if (rc != PS_OK) return rc;
@@ -91,12 +91,17 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     a.raster = t.raster;
     a.in_bytes = (unsigned)((size_t)dm.N * dm.Cb * dm.H * dm.W * kBlock * dm.es);
     a.wt_bytes = (unsigned)((size_t)dm.Kb * dm.NB * kBlock * kBlock * dm.es);
-    if (t.c_split > 1) {
+    a.out_elems = dm.M * dm.K;
+    a.partial = t.c_split > 1 ? ws : nullptr;
+    if (t.c_split > 1 && !ws) {
         rc = launch_fill_zero(out, (size_t)dm.M * dm.K, st);
         if (rc != PS_OK) return rc;
     }
     sh->launch(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
-    return hip_status(hipGetLastError());
+    rc = hip_status(hipGetLastError());
+    if (rc != PS_OK) return rc;
+    if (t.c_split > 1 && ws) rc = launch_reduce_planes(ws, out, (size_t)dm.M * dm.K, t.c_split, st);
+    return rc;
 }
 
 }  // namespace ps
@@ -143,7 +148,7 @@ extern "C" int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const
     if (rc != PS_OK) return rc;
     if (!t || !in_blk || !wt_blk || !out_blk) return PS_EINVAL;
     if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk)) return PS_EINVAL;
-    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, (hipStream_t)stream);
+    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const void *wt_blk, void *out_blk,
@@ -154,6 +159,36 @@ extern "C" int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const vo
     int rc = ps_tile_select(d, &t, &us);
     if (rc != PS_OK) return rc;
     return ps_conv2d_fwd_tile(d, &t, in_blk, wt_blk, out_blk, stream);
+}
+
+extern "C" size_t ps_workspace_bytes(const ps_conv_desc *d, const ps_tile *t)
+{
+    Dims dm;
+    if (make_dims(d, &dm) != PS_OK || !t || tile_valid(dm, *t) != PS_OK) return 0;
+    return t->c_split > 1 ? (size_t)t->c_split * (size_t)dm.M * dm.K * 4 : 0;
+}
+
+extern "C" int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
+                                void *out_blk, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk) || !aligned16(workspace)) return PS_EINVAL;
+    ps_tile pick;
+    if (!t) {
+        double us;
+        rc = ps_tile_select_ws(d, workspace ? workspace_bytes : 0, &pick, &us);
+        if (rc != PS_OK) return rc;
+        t = &pick;
+    }
+    rc = tile_valid(dm, *t);
+    if (rc != PS_OK) return rc;
+    const size_t need = t->c_split > 1 ? (size_t)t->c_split * (size_t)dm.M * dm.K * 4 : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PS_EINVAL;
+    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr,
+                       (hipStream_t)stream);
 }
 
 extern "C" int ps_tile_valid(const ps_conv_desc *d, const ps_tile *t)

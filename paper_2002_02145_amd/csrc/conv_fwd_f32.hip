@@ -45,4 +45,23 @@ int launch_fill_zero(float *p, size_t n, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
+// out = sum over planes of partial[plane][.]; n4 = out elements / 4 (blocked outputs are multiples of 16).
+__global__ __launch_bounds__(256) void reduce_planes_kernel(const floatx4 *__restrict__ partial, floatx4 *__restrict__ out,
+                                                            size_t n4, int planes)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    floatx4 s = partial[i];
+    for (int p = 1; p < planes; ++p) s += partial[(size_t)p * n4 + i];
+    out[i] = s;
+}
+
+int launch_reduce_planes(const float *partial, float *out, size_t n, int planes, hipStream_t stream)
+{
+    const size_t n4 = n / 4;
+    hipLaunchKernelGGL(reduce_planes_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
+                       reinterpret_cast<const floatx4 *>(partial), reinterpret_cast<floatx4 *>(out), n4, planes);
+    return hip_status(hipGetLastError());
+}
+
 }  // namespace ps

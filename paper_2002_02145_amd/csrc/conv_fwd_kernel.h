@@ -59,6 +59,8 @@ struct ConvArgs {
     int n_mt, n_kt;
     int raster;
     unsigned in_bytes, wt_bytes;
+    float *partial;        // split reduction with a workspace: [c_split][out elements], else nullptr (atomics)
+    long long out_elems;   // N*K*P*Q
 };
 
 constexpr unsigned kOobOffset = 0x80000000u;  // >= any accepted buffer size: such a load returns 0
@@ -121,8 +123,10 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
 {
     const int wk = wave % WK, wm = wave / WK;
     const int half = lane >> 5, l32 = lane & 31;
-    if (a.c_split == 1) {
+    if (a.c_split == 1 || a.partial != nullptr) {
         // A lane holds one pixel and 4 consecutive channels per register quad: one 16-byte store each.
+        // With a workspace, split s stores its partial tile into plane s; a second kernel adds the planes.
+        float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int m = m0 + (wm * TM + tm) * 32 + l32;
@@ -135,7 +139,7 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
                 for (int rq = 0; rq < 4; ++rq) {
                     const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
                     if (ofm >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
-                    float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
+                    float *o = base + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
                     const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
                                        acc[tk][tm][rq * 4 + 3]};
                     *reinterpret_cast<floatx4 *>(o) = v;
@@ -144,7 +148,7 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
         }
         return;
     }
-    // Split reduction: partial tiles are added into the cleared output with fp32 atomics.  Issued from
+    // Split reduction without a workspace: partial tiles are added into the cleared output with fp32 atomics.  Issued from
     // the accumulator layout, one atomic instruction would touch 64 different 64-byte lines; each wave
     // therefore turns its 32x32 tile around in a private LDS patch so that 16 consecutive lanes cover
     // one pixel's 16-channel line and an instruction adds into 4 whole lines.

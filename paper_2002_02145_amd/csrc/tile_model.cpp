@@ -56,7 +56,7 @@ const Chip kChip;
 // one XCD -> that XCD's L2 if they fit, else the Infinity Cache, else HBM.  The cost is the time the
 // slowest level needs for the bytes it has to move (Eq. 1 with latency folded into per-workgroup
 // fill and launch terms), plus a fraction of the second-slowest for imperfect overlap.
-double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh)
+double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool with_ws)
 {
     const Chip &c = kChip;
     const double M = (double)dm.M;
@@ -88,7 +88,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh)
     // a load issued in iteration b must have landed (ring - 1) iterations later
     const double clk_iter = tiles_wave * mfma_clk / c.steady_eff * waves_res;
     clk_iter_overhead += std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) * nb_pad / waves_res;
-    const double clk_epi = tiles_wave * (t.c_split > 1 ? 900.0 : 250.0);
+    const double clk_epi = tiles_wave * (t.c_split > 1 && !with_ws ? 900.0 : 250.0);
     const double rounds = std::ceil(per_cu / occ);
     const double t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk) / c.clock_hz;
 
@@ -116,9 +116,12 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh)
     const double far_bw = total <= 0.7 * c.mall_bytes ? c.mall_bw : c.hbm_bw;
     double t_mem = std::max(cu_bytes / c.l2_bw, beyond_l2 / far_bw);
     double t_extra = 0.0;
-    if (t.c_split > 1) {
+    if (t.c_split > 1 && !with_ws) {
         t_mem += out_bytes * t.c_split / c.atomic_bw;   // atomic accumulation of partial tiles
         t_extra = out_bytes / c.hbm_bw * 1e6 + c.launch_us;  // the clearing pass
+    } else if (t.c_split > 1) {
+        t_mem += out_bytes * t.c_split / far_bw;  // partial planes written once ...
+        t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 + c.launch_us;  // ... and added by a second pass
     }
     return (std::max(t_mfma, t_mem) + 0.25 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us + t_extra;
 }
@@ -193,7 +196,7 @@ extern "C" int ps_tile_get(const ps_conv_desc *d, int idx, ps_tile *t)
     return PS_OK;
 }
 
-extern "C" double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t)
+static double cost_of(const ps_conv_desc *d, const ps_tile *t, bool with_ws)
 {
     Dims dm;
     if (make_dims(d, &dm) != PS_OK || !t || ps_tile_valid(d, t) != PS_OK) return -1.0;
@@ -201,11 +204,14 @@ extern "C" double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t)
     const int ns = list_shapes(dm.dtype, shapes, 128);
     for (int i = 0; i < ns; ++i)
         if (shapes[i].kt == t->kt && shapes[i].mt == t->mt && shapes[i].ring == t->ring)
-            return model_cost(dm, *t, shapes[i]);
+            return model_cost(dm, *t, shapes[i], with_ws);
     return -1.0;
 }
 
-extern "C" int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us)
+extern "C" double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t) { return cost_of(d, t, false); }
+extern "C" double ps_tile_cost_ws_us(const ps_conv_desc *d, const ps_tile *t) { return cost_of(d, t, true); }
+
+static int select_best(const ps_conv_desc *d, bool with_ws, size_t ws_bytes, ps_tile *best, double *modelled_us)
 {
     Dims dm;
     int rc = make_dims(d, &dm);
@@ -213,17 +219,31 @@ extern "C" int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *mode
     if (!best) return PS_EINVAL;
     std::vector<Cand> c;
     enumerate(dm, c);
-    if (c.empty()) return PS_EUNSUPPORTED;
     double bu = 1e300;
-    int bi = 0;
+    int bi = -1;
     for (size_t i = 0; i < c.size(); ++i) {
-        const double u = model_cost(dm, c[i].t, c[i].sh);
+        bool ws = with_ws;
+        if (with_ws && c[i].t.c_split > 1 &&
+            (size_t)c[i].t.c_split * (size_t)dm.M * dm.K * 4 > ws_bytes)
+            continue;  // its partial planes do not fit the caller's workspace
+        const double u = model_cost(dm, c[i].t, c[i].sh, ws);
         if (u < bu) {
             bu = u;
             bi = (int)i;
         }
     }
+    if (bi < 0) return PS_EUNSUPPORTED;
     *best = c[bi].t;
     if (modelled_us) *modelled_us = bu;
     return PS_OK;
+}
+
+extern "C" int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us)
+{
+    return select_best(d, false, 0, best, modelled_us);
+}
+
+extern "C" int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *best, double *modelled_us)
+{
+    return select_best(d, true, workspace_bytes, best, modelled_us);
 }

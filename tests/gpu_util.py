@@ -29,12 +29,17 @@ def blocked_inputs(shape, x: np.ndarray, w: np.ndarray, dtype: int = ps.PS_F32):
     return d, xb, wb
 
 
-def run_conv(shape, x, w, dtype: int = ps.PS_F32, tile=None, poison: float = float("nan")) -> np.ndarray:
+def run_conv(shape, x, w, dtype: int = ps.PS_F32, tile=None, poison: float = float("nan"), ws: bool = False) -> np.ndarray:
     """Full path through the C ABI: transforms, convolution, inverse transform.  Returns NKPQ fp32.
-    The blocked output buffer is pre-filled with `poison` so that unwritten elements show."""
+    The blocked output buffer is pre-filled with `poison` so that unwritten elements show.
+    ws=True goes through ps_conv2d_fwd_ws with a poisoned workspace of exactly the needed size."""
     d, xb, wb = blocked_inputs(shape, x, w, dtype)
     ob = torch.full((ps.ps_blocked_out_bytes(d) // 4,), poison, dtype=torch.float32, device=DEV)
-    if tile is None:
+    if ws:
+        need = ps.ps_workspace_bytes(d, tile) if tile is not None else 64 << 20
+        buf = torch.full((max(need, 16) // 4,), poison, dtype=torch.float32, device=DEV)
+        ps.ps_conv2d_fwd_ws(d, tile, xb, wb, ob, buf if need else None, need)
+    elif tile is None:
         ps.ps_conv2d_fwd(d, xb, wb, ob)
     else:
         ps.ps_conv2d_fwd_tile(d, tile, xb, wb, ob)

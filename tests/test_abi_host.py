@@ -83,6 +83,13 @@ def test_tile_enumerator_and_model(ps):
             assert ps.ps_tile_valid(d, t)
             assert nb % t.c_split == 0
             assert ps.ps_tile_cost_us(d, t) > 0
+        for t in tiles:
+            assert ps.ps_workspace_bytes(d, t) == (0 if t.c_split == 1 else t.c_split * shape.N * shape.K * shape.P * shape.Q * 4)
+            assert ps.ps_tile_cost_ws_us(d, t) > 0
+        bw, usw = ps.ps_tile_select_ws(d, 0)
+        assert bw.c_split == 1                       # no workspace: only unsplit tiles compete
+        bw, usw = ps.ps_tile_select_ws(d, 1 << 40)
+        assert usw == pytest.approx(min(ps.ps_tile_cost_ws_us(d, t) for t in tiles))
         best, us = ps.ps_tile_select(d)
         costs = [ps.ps_tile_cost_us(d, t) for t in tiles]
         assert us == pytest.approx(min(costs))

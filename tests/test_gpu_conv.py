@@ -41,7 +41,13 @@ def test_every_candidate_tile_matches_oracle(shape):
             got = run_conv(shape, x, w, dtype, t)
             err = oracle.normalised_error(got, out, mag)
             assert err <= TOL[dtype], f"{shape.name} dtype={dtype} {t}: err {err}"
+            if t.c_split > 1:                       # same split through the workspace path
+                got = run_conv(shape, x, w, dtype, t, ws=True)
+                err = oracle.normalised_error(got, out, mag)
+                assert err <= TOL[dtype], f"{shape.name} dtype={dtype} {t} (workspace): err {err}"
         got = run_conv(shape, x, w, dtype)          # the model's pick through ps_conv2d_fwd
+        assert oracle.normalised_error(got, out, mag) <= TOL[dtype]
+        got = run_conv(shape, x, w, dtype, ws=True)  # the model's pick through ps_conv2d_fwd_ws
         assert oracle.normalised_error(got, out, mag) <= TOL[dtype]
 
 
@@ -107,7 +113,7 @@ def test_resnet50_sweep(dtype):
     from gpu_util import run_conv
     for i, shape in enumerate(wl.resnet50_layers()):
         x, w = _prep(shape, wl.relu_like, wl.sweep_seed(i), dtype)
-        got = run_conv(shape, x, w, dtype)
+        got = run_conv(shape, x, w, dtype, ws=True)      # the configuration bench.py times
         n = i % shape.N
         out, mag = oracle.conv2d_fwd(shape, x, w, images=(n, n + 1))
         err = oracle.normalised_error(got[n:n + 1], out[n:n + 1], mag[n:n + 1])
@@ -134,3 +140,12 @@ def test_invalid_arguments_launch_nothing():
     with pytest.raises(ps.PsError) as e:
         ps.ps_conv2d_fwd_tile(d, ps.Tile(64, 128, 2, 5, 0), buf, buf, buf)   # 36 batch elements % 5 != 0
     assert e.value.status == ps.PS_EUNSUPPORTED
+    split = ps.Tile(64, 64, 2, 2, 0)
+    need = ps.ps_workspace_bytes(d, split)
+    assert need == 2 * 64 * 14 * 14 * 4
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_conv2d_fwd_ws(d, split, buf, buf, buf, buf, need - 16)          # workspace too small
+    assert e.value.status == ps.PS_EINVAL
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_conv2d_fwd_ws(d, split, buf, buf, buf, None, 0)
+    assert e.value.status == ps.PS_EINVAL
