@@ -97,7 +97,14 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
         rc = launch_fill_zero(out, (size_t)dm.M * dm.K, st);
         if (rc != PS_OK) return rc;
     }
-    sh->launch(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
+    a.plane_bytes = dm.H * dm.W * kBlock * dm.es;
+    // filter size baked into the loop when a specialised kernel exists and splits fall on c-block boundaries
+    LaunchFn fn = sh->launch;
+    if (dm.R == dm.S && a.nb_split % (dm.R * dm.S) == 0) {
+        if (dm.R == 1 && sh->launch_1x1) fn = sh->launch_1x1;
+        if (dm.R == 3 && sh->launch_3x3) fn = sh->launch_3x3;
+    }
+    fn(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
     rc = hip_status(hipGetLastError());
     if (rc != PS_OK) return rc;
     if (t.c_split > 1 && ws) rc = launch_reduce_planes(ws, out, (size_t)dm.M * dm.K, t.c_split, st);

@@ -6,23 +6,21 @@ namespace ps {
 //               KT   MT  WK WM NBUF       wave tile (channels x pixels)
 // Ring depths: a load has (NBUF - 1) iterations to land, and an iteration lasts 512 matrix-core cycles
 // per 32x32 tile a wave owns, so the small wave tiles get the deeper rings.
-#define PS_RINGS_24(KT, MT, WK, WM) PS_F32_SHAPE(KT, MT, WK, WM, 2), PS_F32_SHAPE(KT, MT, WK, WM, 4)
-#define PS_RINGS_48(KT, MT, WK, WM) PS_F32_SHAPE(KT, MT, WK, WM, 4), PS_F32_SHAPE(KT, MT, WK, WM, 8)
-static const ShapeEntry kF32Shapes[] = {
-    PS_RINGS_24(256, 128, 4, 2),  // 64 x 64, 8 waves
-    PS_RINGS_24(256, 64, 4, 1),   // 64 x 64
-    PS_RINGS_24(128, 128, 2, 2),  // 64 x 64
-    PS_RINGS_24(64, 256, 1, 4),   // 64 x 64
-    PS_RINGS_24(128, 64, 2, 2),   // 64 x 32
-    PS_RINGS_24(64, 128, 2, 2),   // 32 x 64
-    PS_F32_SHAPE(128, 64, 2, 2, 8), PS_F32_SHAPE(64, 128, 2, 2, 8),
-    PS_F32_SHAPE(64, 64, 2, 2, 2),
-    PS_RINGS_48(64, 64, 2, 2),    // 32 x 32
-    PS_RINGS_48(128, 32, 4, 1),   // 32 x 32
-    PS_RINGS_48(32, 128, 1, 4),   // 32 x 32
-    PS_RINGS_48(64, 32, 2, 1),    // 32 x 32, 2 waves
-    PS_RINGS_48(32, 64, 1, 2),    // 32 x 32, 2 waves
-};
+#define PS_F32_SHAPE_LIST(X)                                     \
+    X(256, 128, 4, 2, 2) X(256, 128, 4, 2, 4) /* 64 x 64, 8 waves */ \
+    X(256, 64, 4, 1, 2) X(256, 64, 4, 1, 4)   /* 64 x 64 */          \
+    X(128, 128, 2, 2, 2) X(128, 128, 2, 2, 4) /* 64 x 64 */          \
+    X(64, 256, 1, 4, 2) X(64, 256, 1, 4, 4)   /* 64 x 64 */          \
+    X(128, 64, 2, 2, 2) X(128, 64, 2, 2, 4) X(128, 64, 2, 2, 8) /* 64 x 32 */ \
+    X(64, 128, 2, 2, 2) X(64, 128, 2, 2, 4) X(64, 128, 2, 2, 8) /* 32 x 64 */ \
+    X(64, 64, 2, 2, 2) X(64, 64, 2, 2, 4) X(64, 64, 2, 2, 8)    /* 32 x 32 */ \
+    X(128, 32, 4, 1, 4) X(128, 32, 4, 1, 8)   /* 32 x 32 */          \
+    X(32, 128, 1, 4, 4) X(32, 128, 1, 4, 8)   /* 32 x 32 */          \
+    X(64, 32, 2, 1, 4) X(64, 32, 2, 1, 8)     /* 32 x 32, 2 waves */ \
+    X(32, 64, 1, 2, 4) X(32, 64, 1, 2, 8)     /* 32 x 32, 2 waves */
+
+#define PS_TABLE_ROW(KT, MT, WK, WM, NBUF) PS_F32_SHAPE(KT, MT, WK, WM, NBUF),
+static const ShapeEntry kF32Shapes[] = {PS_F32_SHAPE_LIST(PS_TABLE_ROW)};
 
 const ShapeEntry *f32_shapes(int *count)
 {

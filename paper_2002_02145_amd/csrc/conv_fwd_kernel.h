@@ -59,6 +59,7 @@ struct ConvArgs {
     int n_mt, n_kt;
     int raster;
     unsigned in_bytes, wt_bytes;
+    int plane_bytes;       // bytes of one [H][W][16] c-block plane of the input
     float *partial;        // split reduction with a workspace: [c_split][out elements], else nullptr (atomics)
     long long out_elems;   // N*K*P*Q
 };
@@ -211,9 +212,50 @@ struct F32Shape {
     static_assert((D - 2) * LPE <= 63, "vmcnt range");
 };
 
-template <int KT, int MT, int WK, int WM, int NBUF>
+// Loads of batch element e (counted from the start of the workgroup's range, b0 already added by the
+// caller's loop) into ring slot `slot`, for the baked-filter path: the tap (e % NTAP) and c-block increment
+// (e / NTAP) are compile-time after unrolling, per-lane offsets come precomputed per tap, everything else is
+// scalar arithmetic.  An element beyond the range gets descriptors of size 0, i.e. reads zeros.
+// (A __device__ function rather than a lambda of the kernel: lambdas are also compiled for the host,
+// where buffer descriptors cannot be built.)
+template <class Sh, int NBUF, int NTAP, int APW, int WPW>
+__device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, const unsigned (&vtap)[APW][NTAP],
+                                               const int (&wsoff)[WPW], const bool (&wok)[WPW], unsigned lane16,
+                                               int wave, int slot, int e, int b0, int cb0)
+{
+    constexpr int NW = Sh::NW;
+    const int tap = e % NTAP, cbi = e / NTAP;
+    const bool valid = b0 + e < a.nb_split;
+    const __amdgpu_buffer_rsrc_t rin_v = make_rsrc(a.in, valid ? a.in_bytes : 0u);
+    const int soff = (cb0 + cbi) * a.plane_bytes;
+    char *sbase = lds + slot * Sh::SLOT;
+#pragma unroll
+    for (int i = 0; i < APW; ++i) {
+        const int grp = i * NW + wave;
+        char *dst = (Sh::PGRP % NW == 0 || grp < Sh::PGRP) ? sbase + grp * 1024 : lds + NBUF * Sh::SLOT;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rin_v, (lds_ptr_t)dst, 16, vtap[i][tap], soff, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < WPW; ++i) {
+        const int blk = i * NW + wave;
+        const __amdgpu_buffer_rsrc_t rwt_v = make_rsrc(a.wt, (valid & wok[i]) ? a.wt_bytes : 0u);
+        char *dst = (Sh::WBLK % NW == 0 || blk < Sh::WBLK) ? sbase + Sh::A_BYTES + blk * Sh::WPITCH
+                                                           : lds + NBUF * Sh::SLOT;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt_v, (lds_ptr_t)dst, 16, lane16, wsoff[i] + ((b0 + e) << 10), 0, 0);
+    }
+}
+
+constexpr int ct_gcd(int x, int y) { return y == 0 ? x : ct_gcd(y, x % y); }
+
+// SIDE > 0 bakes a square SIDE x SIDE filter into the loop (R = S = SIDE, split ranges on c-block
+// boundaries): every load's per-lane offset, validity included, is then precomputed per tap, and the loop
+// issues no vector-ALU instruction at all.  That matters because on this hardware each VALU instruction
+// takes about 4 cycles away from the SIMD's matrix pipe (measured: one VALU op per MFMA costs 6 %).
+// SIDE = 0 is the general path (any R, S), which computes offsets and predicates per load.
+template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
 __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvArgs a)
 {
+    constexpr int TAPS = SIDE * SIDE;
     using Sh = F32Shape<KT, MT, WK, WM, NBUF>;
     constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
     constexpr int APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
@@ -294,6 +336,28 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         lcb += wr;
     };
 
+    // ---- loader of the baked-filter path: offsets per tap, validity folded in ----------------------
+    constexpr int NTAP = TAPS > 0 ? TAPS : 1;
+    unsigned vtap[APW][NTAP];
+    int wsoff[WPW];      // byte offset of filter block (kb0 + blk, batch element 0), uniform per wave
+    bool wok[WPW];
+    if constexpr (TAPS > 0) {
+#pragma unroll
+        for (int i = 0; i < APW; ++i)
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t) {
+                const int r = t / SIDE, sx = t % SIDE;
+                const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W);
+                vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 64 + gchunk * 16) : kOobOffset;
+            }
+#pragma unroll
+        for (int i = 0; i < WPW; ++i) {
+            const int blk = i * NW + wave;
+            wok[i] = (Sh::WBLK % NW == 0 || blk < Sh::WBLK) & (kb0 + blk < a.Kb);
+            wsoff[i] = ((kb0 + blk) * a.NB + b_begin) << 10;
+        }
+    }
+    const unsigned lane16 = (unsigned)lane << 4;
     // ---- reader bookkeeping -------------------------------------------------------------
     int paddr[TM], waddr[TK];
 #pragma unroll
@@ -348,22 +412,50 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 
     // ---- pipeline ---------------------------------------------------------------------------
     const int nb = a.nb_split;
+    if constexpr (TAPS > 0) {
+        // unrolled over lcm(NBUF, TAPS) iterations so that ring slot, fragment parity and tap are static
+        constexpr int U = NBUF / ct_gcd(NBUF, TAPS) * TAPS;
+        int cb0 = b_begin / TAPS;
 #pragma unroll
-    for (int e = 0; e < D; ++e) issue_loads(e);  // elements 0..D-1 (zero-filled beyond the range)
-    wait_vm_and_barrier<(D - 1) * LPE>();        // element 0 has landed everywhere
-    read_frags(0, 0);
-
-    // iteration b: slot b % NBUF, fragment parity b % 2; unrolled by NBUF (even) so both are static.
-    // The range is padded up to a multiple of NBUF with zero elements (loads past b_end read zeros).
-    static_assert(NBUF % 2 == 0, "ring size must be even");
-    for (int b0 = 0; b0 < nb; b0 += NBUF) {
+        for (int e = 0; e < D; ++e)
+            issue_baked_fn<Sh, NBUF, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, lane16, wave, e, e, 0, cb0);
+        wait_vm_and_barrier<(D - 1) * LPE>();
+        read_frags(0, 0);
+        for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
 #pragma unroll
-        for (int u = 0; u < NBUF; ++u) {
-            wait_vm_and_barrier<(D - 2) * LPE>();
-            read_frags((u + 1) % NBUF, (u + 1) % 2);
-            issue_loads(u % NBUF);
-            mfmas(u % 2);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int u = 0; u < U; ++u) {
+                wait_vm_and_barrier<(D - 2) * LPE>();
+                read_frags((u + 1) % NBUF, (u + 1) % 2);
+                issue_baked_fn<Sh, NBUF, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, lane16, wave, u % NBUF, u + NBUF,
+                                                         b0, cb0);
+                mfmas(u % 2);
+                // order within the iteration: after each of the first MFMAs one LDS read and one load, so
+                // that the next fragments are requested early and into the other register set
+#pragma unroll
+                for (int i = 0; i < TK * TM * 8; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < D; ++e) issue_loads(e);  // elements 0..D-1 (zero-filled beyond the range)
+        wait_vm_and_barrier<(D - 1) * LPE>();        // element 0 has landed everywhere
+        read_frags(0, 0);
+        // iteration b: slot b % NBUF, fragment parity b % 2; unrolled by NBUF (even) so both are static.
+        // The range is padded up to a multiple of NBUF with zero elements (loads past b_end read zeros).
+        for (int b0 = 0; b0 < nb; b0 += NBUF) {
+#pragma unroll
+            for (int u = 0; u < NBUF; ++u) {
+                wait_vm_and_barrier<(D - 2) * LPE>();
+                read_frags((u + 1) % NBUF, (u + 1) % 2);
+                issue_loads(u % NBUF);
+                mfmas(u % 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -372,19 +464,23 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 }
 
 // One compiled kernel shape and how to launch it.
+typedef void (*LaunchFn)(const ConvArgs &, unsigned grid, hipStream_t);
 struct ShapeEntry {
     int dtype, kt, mt, ring, threads, lds_bytes;
-    void (*launch)(const ConvArgs &, unsigned grid, hipStream_t);
+    LaunchFn launch;      // any filter size
+    LaunchFn launch_1x1;  // R = S = 1 baked in (nullptr if not compiled)
+    LaunchFn launch_3x3;  // R = S = 3 baked in
 };
 
-template <int KT, int MT, int WK, int WM, int NBUF>
+template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
 void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((conv_fwd_f32_kernel<KT, MT, WK, WM, NBUF>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
+    hipLaunchKernelGGL((conv_fwd_f32_kernel<KT, MT, WK, WM, NBUF, SIDE>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
 
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
     {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES,                      \
-     &launch_f32<KT, MT, WK, WM, NBUF>}
+     &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
+     &launch_f32<KT, MT, WK, WM, NBUF, 3>}
 
 }  // namespace ps
