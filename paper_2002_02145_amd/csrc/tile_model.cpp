@@ -42,13 +42,33 @@ struct Chip {
     double l2_bw = 14.0e12;                   // L2 -> LDS, all XCDs
     double atomic_bw = 0.35e12;               // fp32 atomic adds (resolved memory-side across XCDs), payload bytes/s
     double mfma_flop_clk_cu[2] = {256.0, 4096.0};  // f32, bf16
-    double steady_eff = 0.84;                 // matrix-core issue efficiency of the pipelined loop
-    double load_latency_clk = 1500.0;         // global load to LDS, L2 hit under load
-    double fill_clk = 6000.0;                 // first loads of a workgroup (nothing to overlap with)
+    double steady_eff = 0.84;                 // matrix-core issue efficiency of the general loop (VALU address work)
+    double steady_eff_baked = 0.97;           // ... of the loops with a baked filter size (no VALU work)
+    double load_latency_clk = 1150.0;         // global load to LDS, L2 hit under load
+    double fill_clk = 4500.0;                 // first loads of a workgroup (nothing to overlap with)
     double launch_us = 1.5;
 };
 
 const Chip kChip;
+
+// The kernels with a baked 1x1 or 3x3 filter issue no vector-ALU work in their loop; their loop is unrolled
+// over lcm(ring, R*S) batch elements and the range is padded to a multiple of that.
+bool baked_filter(const Dims &dm, int nb_split)
+{
+    return dm.dtype == PS_F32 && dm.R == dm.S && (dm.R == 1 || dm.R == 3) && nb_split % (dm.R * dm.S) == 0;
+}
+
+int padded_elems(const Dims &dm, int ring, int nb_split)
+{
+    int unit = ring;
+    if (baked_filter(dm, nb_split)) {
+        const int taps = dm.R * dm.S;
+        int g = ring, h = taps;
+        while (h) { const int r = g % h; g = h; h = r; }
+        unit = ring / g * taps;
+    }
+    return (nb_split + unit - 1) / unit * unit;
+}
 
 // Working sets of the tile's data reuses, and the level each one is served from (the analogue of
 // Algorithms 1 and 2): accumulators -> registers, one batch element of pixels and filters -> LDS
@@ -63,7 +83,8 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double n_mt = std::ceil(M / t.mt), n_kt = std::ceil((double)dm.K / t.kt);
     const double nwg = n_mt * n_kt * t.c_split;
     const double nb_split = (double)dm.NB / t.c_split;
-    const double nb_pad = std::ceil(nb_split / t.ring) * t.ring;  // zero elements pad the range
+    const double nb_pad = padded_elems(dm, t.ring, dm.NB / t.c_split);  // zero elements pad the range
+    const bool baked = baked_filter(dm, dm.NB / t.c_split);
     const double es = dm.es;
     const double waves_wg = sh.threads / 64.0;
 
@@ -80,17 +101,22 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double per_cu = std::ceil(nwg / c.cus);
     const double per_simd = std::ceil(per_cu * waves_wg / 4.0);
     const double mfma_clk = dm.dtype == PS_F32 ? 64.0 * 8.0 : 32.0;  // per 32x32 tile per batch element
-    const double clk_wave = tiles_wave * mfma_clk * nb_pad / c.steady_eff;
+    const double eff = baked ? c.steady_eff_baked : c.steady_eff;
+    const double clk_wave = tiles_wave * mfma_clk * nb_pad / eff;
     // per batch element a wave also pays a barrier and the issue of its loads and LDS reads; with a
     // single resident wave per SIMD nothing hides that
     const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
     double clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * nb_pad;
-    // a load issued in iteration b must have landed (ring - 1) iterations later
-    const double clk_iter = tiles_wave * mfma_clk / c.steady_eff * waves_res;
-    clk_iter_overhead += std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) * nb_pad / waves_res;
+    // a load issued in iteration b must have landed (ring - 1) iterations later: the part of the latency
+    // the ring does not cover stalls every wave of the SIMD, and latency varies, so a thin margin still costs
+    const double clk_iter = tiles_wave * mfma_clk / eff * waves_res;  // wall clock of one iteration
+    const double cover = (t.ring - 1) * clk_iter / c.load_latency_clk;
+    const double stall = std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) + 0.50 * clk_iter * std::exp(-cover);
+    clk_iter_overhead += stall * nb_pad / waves_res;
     const double clk_epi = tiles_wave * (t.c_split > 1 && !with_ws ? 900.0 : 250.0);
     const double rounds = std::ceil(per_cu / occ);
-    const double t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk) / c.clock_hz;
+    const double t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk +
+                           per_cu * (t.ring - 2) * 250.0) / c.clock_hz;  // a deeper ring takes longer to fill, per workgroup
 
     // ---- bytes that cross each level --------------------------------------------------------------
     const double in_bytes = (double)dm.N * dm.Cb * dm.H * dm.W * 16.0 * es;
@@ -123,7 +149,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         t_mem += out_bytes * t.c_split / far_bw;  // partial planes written once ...
         t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 + c.launch_us;  // ... and added by a second pass
     }
-    return (std::max(t_mfma, t_mem) + 0.25 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us + t_extra;
+    return (std::max(t_mfma, t_mem) + 0.12 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us + t_extra;
 }
 
 struct Cand {
@@ -151,10 +177,10 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
             int shallowest = 1 << 30;
             for (int j = 0; j < ns; ++j)
                 if (shapes[j].kt == s.kt && shapes[j].mt == s.mt) {
-                    if (shapes[j].ring <= nbs && nbs % shapes[j].ring == 0) any_exact = true;
+                    if (padded_elems(dm, shapes[j].ring, nbs) == nbs) any_exact = true;
                     shallowest = std::min(shallowest, shapes[j].ring);
                 }
-            const bool exact = s.ring <= nbs && nbs % s.ring == 0;
+            const bool exact = padded_elems(dm, s.ring, nbs) == nbs;
             if (any_exact ? !exact : s.ring != shallowest) continue;
             if (sp > 1 && base_wg * sp > 8 * 256) continue;  // split only under-filled grids
             for (int raster = 0; raster < 2; ++raster) {
