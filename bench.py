@@ -64,14 +64,15 @@ def _time_each(fn, launches: int):
 # HBM-side bytes per launch of the headline kernel from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each
 # scaled by a reference copy; see profiles/), keyed by a digest of the kernel sources they were taken with.
 # A different digest means the kernel changed since: traffic is then reported as null.
-MEASURED_TRAFFIC = {"f32": ("0e67f270330db260", 46446244)}
+MEASURED_TRAFFIC = {"f32": ("3189dabb09c1a1b7", 46651177)}
 
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=1000,
+                    help="untimed steps first; the GPU needs tens of milliseconds of load to reach its sustained clocks")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -119,7 +120,7 @@ def main(argv=None) -> int:
 
     wall_ms, ev_ms = _time_steps(step, a.steps, a.warmup)
     gflops = shape.flops / (wall_ms * 1e-3) * 1e-9
-    each_ms = _time_each(step, min(200, max(20, a.steps)))
+    each_ms = _time_each(step, min(500, max(20, a.steps)))
     kernel_tflops = shape.flops / (each_ms * 1e-3) * 1e-12
     from paper_2002_02145_amd.profile_summary import kernel_source_digest
     digest, tbytes = MEASURED_TRAFFIC.get(a.dtype, (None, None))
@@ -180,7 +181,7 @@ def main(argv=None) -> int:
             wsb = ps.ps_workspace_bytes(dl, t)
             wsl = torch.empty(max(wsb, 16) // 4, dtype=torch.float32, device=dev)
             reps = max(20, min(300, int(20e-3 / (L.flops_issued / (PEAK_TFLOPS[a.dtype] * 1e12 * 0.3)))))
-            _, ms = _time_steps(lambda: ps.ps_conv2d_fwd_ws(dl, t, xi, wi, oi, wsl, wsb), reps, 5)
+            _, ms = _time_steps(lambda: ps.ps_conv2d_fwd_ws(dl, t, xi, wi, oi, wsl, wsb), 2 * reps, reps)
             tf = L.flops / (ms * 1e-3) * 1e-12
             layers.append({"layer": L.name, "us": round(ms * 1e3, 2), "TFLOP/s": round(tf, 2),
                            "frac_mfma_peak": round(tf / PEAK_TFLOPS[a.dtype], 4),
