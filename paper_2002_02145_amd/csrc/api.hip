@@ -37,6 +37,10 @@ int make_dims(const ps_conv_desc *d, Dims *o)
     return PS_OK;
 }
 
+// 7x7 filter over at most 4 input channels (a network stem): the fp32 kernels pack 4 taps x 4 channels into
+// one 16-lane batch element.
+bool packs_taps(const Dims &dm) { return dm.dtype == PS_F32 && dm.C <= 4 && dm.R == 7 && dm.S == 7; }
+
 const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 {
     int n = 0;
@@ -103,6 +107,10 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     if (dm.R == dm.S && a.nb_split % (dm.R * dm.S) == 0) {
         if (dm.R == 1 && sh->launch_1x1) fn = sh->launch_1x1;
         if (dm.R == 3 && sh->launch_3x3) fn = sh->launch_3x3;
+    }
+    if (packs_taps(dm) && t.c_split == 1 && sh->launch_7x7p) {
+        fn = sh->launch_7x7p;
+        a.nb_split = 14;  // 7 filter rows x 2 groups of 4 taps; a.NB stays 49 for filter addressing
     }
     fn(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
     rc = hip_status(hipGetLastError());

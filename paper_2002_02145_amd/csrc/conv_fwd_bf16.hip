@@ -196,7 +196,7 @@ void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
 
 #define PS_BF16_SHAPE(KT, MT, WK, WM, NBUF, G)                                                          \
     {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES,                 \
-     &launch_bf16<KT, MT, WK, WM, NBUF, G>, nullptr, nullptr}
+     &launch_bf16<KT, MT, WK, WM, NBUF, G>, nullptr, nullptr, nullptr}
 #define PS_BF16_RINGS(KT, MT, WK, WM, G) PS_BF16_SHAPE(KT, MT, WK, WM, 2, G), PS_BF16_SHAPE(KT, MT, WK, WM, 4, G)
 
 //                 KT   MT  WK WM  G        wave tile (channels x pixels)

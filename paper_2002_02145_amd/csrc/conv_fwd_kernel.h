@@ -218,16 +218,16 @@ struct F32Shape {
 // scalar arithmetic.  An element beyond the range gets descriptors of size 0, i.e. reads zeros.
 // (A __device__ function rather than a lambda of the kernel: lambdas are also compiled for the host,
 // where buffer descriptors cannot be built.)
-template <class Sh, int NBUF, int NTAP, int APW, int WPW>
+template <class Sh, int NBUF, int NTAP, int APW, int WPW, bool PACK4>
 __device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, const unsigned (&vtap)[APW][NTAP],
-                                               const int (&wsoff)[WPW], const bool (&wok)[WPW], unsigned lane16,
-                                               int wave, int slot, int e, int b0, int cb0)
+                                               const int (&wsoff)[WPW], const bool (&wok)[WPW],
+                                               const unsigned (&vw)[2], int wave, int slot, int e, int b0, int cb0)
 {
     constexpr int NW = Sh::NW;
     const int tap = e % NTAP, cbi = e / NTAP;
     const bool valid = b0 + e < a.nb_split;
     const __amdgpu_buffer_rsrc_t rin_v = make_rsrc(a.in, valid ? a.in_bytes : 0u);
-    const int soff = (cb0 + cbi) * a.plane_bytes;
+    const int soff = PACK4 ? 0 : (cb0 + cbi) * a.plane_bytes;
     char *sbase = lds + slot * Sh::SLOT;
 #pragma unroll
     for (int i = 0; i < APW; ++i) {
@@ -241,7 +241,9 @@ __device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, con
         const __amdgpu_buffer_rsrc_t rwt_v = make_rsrc(a.wt, (valid & wok[i]) ? a.wt_bytes : 0u);
         char *dst = (Sh::WBLK % NW == 0 || blk < Sh::WBLK) ? sbase + Sh::A_BYTES + blk * Sh::WPITCH
                                                            : lds + NBUF * Sh::SLOT;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt_v, (lds_ptr_t)dst, 16, lane16, wsoff[i] + ((b0 + e) << 10), 0, 0);
+        // tap-packed mode: filter row r = tap / 2 of the 7x7 filter, per-lane offsets pick the taps 4g .. 4g+3
+        const int wso = PACK4 ? wsoff[i] + (tap / 2) * 7 * 1024 : wsoff[i] + ((b0 + e) << 10);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt_v, (lds_ptr_t)dst, 16, vw[PACK4 ? tap % 2 : 0], wso, 0, 0);
     }
 }
 
@@ -255,7 +257,13 @@ constexpr int ct_gcd(int x, int y) { return y == 0 ? x : ct_gcd(y, x % y); }
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
 __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvArgs a)
 {
-    constexpr int TAPS = SIDE * SIDE;
+    // SIDE = 7 is the tap-packed mode for inputs with at most 4 channels (one c-block whose lanes 4..15 are
+    // zero padding, e.g. an RGB network stem): a batch element then holds channels 0..3 of four horizontally
+    // adjacent taps (4 taps x 4 channels = the 16 reduction lanes) instead of 16 channels of one tap, so a
+    // 7x7 filter takes 7 rows x 2 tap groups = 14 elements instead of 49.  Pixels and filter rows are gathered
+    // accordingly from the ordinary blocked tensors: only the per-lane load offsets differ.
+    constexpr bool PACK4 = SIDE == 7;
+    constexpr int TAPS = PACK4 ? 14 : SIDE * SIDE;
     using Sh = F32Shape<KT, MT, WK, WM, NBUF>;
     constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
     constexpr int APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
@@ -346,9 +354,13 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         for (int i = 0; i < APW; ++i)
 #pragma unroll
             for (int t = 0; t < TAPS; ++t) {
-                const int r = t / SIDE, sx = t % SIDE;
-                const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W);
-                vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 64 + gchunk * 16) : kOobOffset;
+                // ordinary: tap (r, sx), this lane fetches chunk `gchunk` of the pixel's 16 channels;
+                // tap-packed: row r, taps 4g .. 4g+3, this lane fetches channels 0..3 of tap 4g + gchunk
+                const int r = PACK4 ? t / 2 : t / SIDE;
+                const int sx = PACK4 ? (t % 2) * 4 + gchunk : t % SIDE;
+                const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W) &
+                                (sx < SIDE);
+                vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 64 + (PACK4 ? 0 : gchunk * 16)) : kOobOffset;
             }
 #pragma unroll
         for (int i = 0; i < WPW; ++i) {
@@ -357,7 +369,14 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
             wsoff[i] = ((kb0 + blk) * a.NB + b_begin) << 10;
         }
     }
-    const unsigned lane16 = (unsigned)lane << 4;
+    // per-lane offset of a filter load inside its 1 KB block: lane*16 normally; tap-packed, LDS row
+    // c' = lane/4 = 4*j + c is row c of the block of tap 4g + j
+    unsigned vw[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        const int cp = lane >> 2, j = cp >> 2, c = cp & 3, sx = 4 * g + j;
+        vw[g] = !PACK4 ? (unsigned)lane << 4 : sx < 7 ? (unsigned)(sx * 1024 + c * 64 + (lane & 3) * 16) : kOobOffset;
+    }
     // ---- reader bookkeeping -------------------------------------------------------------
     int paddr[TM], waddr[TK];
 #pragma unroll
@@ -418,7 +437,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         int cb0 = b_begin / TAPS;
 #pragma unroll
         for (int e = 0; e < D; ++e)
-            issue_baked_fn<Sh, NBUF, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, lane16, wave, e, e, 0, cb0);
+            issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
         wait_vm_and_barrier<(D - 1) * LPE>();
         read_frags(0, 0);
         for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
@@ -426,7 +445,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
             for (int u = 0; u < U; ++u) {
                 wait_vm_and_barrier<(D - 2) * LPE>();
                 read_frags((u + 1) % NBUF, (u + 1) % 2);
-                issue_baked_fn<Sh, NBUF, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, lane16, wave, u % NBUF, u + NBUF,
+                issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,
                                                          b0, cb0);
                 mfmas(u % 2);
                 // order within the iteration: after each of the first MFMAs one LDS read and one load, so
@@ -470,6 +489,7 @@ struct ShapeEntry {
     LaunchFn launch;      // any filter size
     LaunchFn launch_1x1;  // R = S = 1 baked in (nullptr if not compiled)
     LaunchFn launch_3x3;  // R = S = 3 baked in
+    LaunchFn launch_7x7p; // R = S = 7, C <= 4: tap-packed
 };
 
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
@@ -481,6 +501,6 @@ void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
     {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES,                      \
      &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
-     &launch_f32<KT, MT, WK, WM, NBUF, 3>}
+     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32<KT, MT, WK, WM, NBUF, 7>}
 
 }  // namespace ps

@@ -55,14 +55,19 @@ const Chip kChip;
 // over lcm(ring, R*S) batch elements and the range is padded to a multiple of that.
 bool baked_filter(const Dims &dm, int nb_split)
 {
+    if (packs_taps(dm)) return nb_split == dm.NB;  // unsplit only
     return dm.dtype == PS_F32 && dm.R == dm.S && (dm.R == 1 || dm.R == 3) && nb_split % (dm.R * dm.S) == 0;
 }
+
+// batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples
+int logical_elems(const Dims &dm, int nb_split) { return baked_filter(dm, nb_split) && packs_taps(dm) ? 14 : nb_split; }
 
 int padded_elems(const Dims &dm, int ring, int nb_split)
 {
     int unit = ring;
     if (baked_filter(dm, nb_split)) {
-        const int taps = dm.R * dm.S;
+        const int taps = packs_taps(dm) ? 14 : dm.R * dm.S;
+        if (packs_taps(dm)) nb_split = 14;  // 7 rows x 2 groups of 4 taps replace the 49 taps
         int g = ring, h = taps;
         while (h) { const int r = g % h; g = h; h = r; }
         unit = ring / g * taps;
@@ -177,10 +182,10 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
             int shallowest = 1 << 30;
             for (int j = 0; j < ns; ++j)
                 if (shapes[j].kt == s.kt && shapes[j].mt == s.mt) {
-                    if (padded_elems(dm, shapes[j].ring, nbs) == nbs) any_exact = true;
+                    if (padded_elems(dm, shapes[j].ring, nbs) == logical_elems(dm, nbs)) any_exact = true;
                     shallowest = std::min(shallowest, shapes[j].ring);
                 }
-            const bool exact = padded_elems(dm, s.ring, nbs) == nbs;
+            const bool exact = padded_elems(dm, s.ring, nbs) == logical_elems(dm, nbs);
             if (any_exact ? !exact : s.ring != shallowest) continue;
             if (sp > 1 && base_wg * sp > 8 * 256) continue;  // split only under-filled grids
             for (int raster = 0; raster < 2; ++raster) {

@@ -13,4 +13,6 @@ EDGE_SHAPES = [
     ConvShape(1, 32, 12, 12, 256, 3, 3, 1, 0, "no_pad_K256"),
     ConvShape(2, 16, 6, 6, 48, 3, 3, 1, 1, "K48_ragged_tile"),
     ConvShape(1, 80, 3, 3, 96, 1, 1, 1, 0, "five_blocks_prime_batch"),  # batch-reduce length 5
+    ConvShape(2, 4, 9, 10, 16, 7, 7, 1, 3, "7x7_C4_stride1"),           # tap-packed path with all 4 lanes real
+    ConvShape(1, 5, 9, 9, 32, 7, 7, 2, 3, "7x7_C5_not_packed"),         # one channel too many for tap packing
 ]

@@ -95,7 +95,7 @@ def test_tile_enumerator_and_model(ps):
         assert us == pytest.approx(min(costs))
         assert best.as_tuple() in {t.as_tuple() for t in tiles}
         # no variant can be modelled faster than the matrix cores allow
-        assert us * 1e-6 >= shape.flops_issued / (157.3e12 if dtype == ps.PS_F32 else 2.5e15) * 0.999
+        assert us * 1e-6 >= shape.flops / (157.3e12 if dtype == ps.PS_F32 else 2.5e15) * 0.999
         with pytest.raises(ps.PsError):
             ps.ps_tile_get(d, n)
     assert not ps.ps_tile_valid(ps.ConvDesc.of(wl.CFG1), ps.Tile(128, 128, 2, 1, 0))   # K = 64 < kt
