@@ -102,6 +102,9 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
         if (rc != PS_OK) return rc;
     }
     a.plane_bytes = dm.H * dm.W * kBlock * dm.es;
+    a.magic_pq = a.PQ == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.PQ);
+    a.magic_q = a.Q == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.Q);
+    a.out_bytes = (unsigned)((size_t)dm.M * dm.K * 4);
     // filter size baked into the loop when a specialised kernel exists and splits fall on c-block boundaries
     LaunchFn fn = sh->launch;
     if (dm.R == dm.S && a.nb_split % (dm.R * dm.S) == 0) {

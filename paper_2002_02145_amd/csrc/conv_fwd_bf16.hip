@@ -72,10 +72,9 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
         const int grp = i * NW + wave;
         const int m = m0 + grp * 32 + (lane >> 1);
         if (grp < Sh::PGRP && m < a.M) {
-            const int n = m / a.PQ;
-            const int pq = m - n * a.PQ;
-            const int p = pq / a.Q;
-            const int q = pq - p * a.Q;
+            int n, pq, p, q;
+            fast_divmod(m, a.PQ, a.magic_pq, n, pq);
+            fast_divmod(pq, a.Q, a.magic_q, p, q);
             h0[i] = p * a.stride - a.pad;
             w0[i] = q * a.stride - a.pad;
             poff[i] = (n * a.Cb * a.H + h0[i]) * a.W + w0[i];

@@ -44,6 +44,7 @@ namespace ps {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 struct ConvArgs {
@@ -60,6 +61,8 @@ struct ConvArgs {
     int raster;
     unsigned in_bytes, wt_bytes;
     int plane_bytes;       // bytes of one [H][W][16] c-block plane of the input
+    unsigned magic_pq, magic_q;  // floor(2^32 / PQ), floor(2^32 / Q) for divisions without the long VALU sequence
+    unsigned out_bytes;
     float *partial;        // split reduction with a workspace: [c_split][out elements], else nullptr (atomics)
     long long out_elems;   // N*K*P*Q
 };
@@ -70,6 +73,19 @@ constexpr int kNumXcd = 8;
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+// n / d for 0 <= n < 2^31 with magic = floor(2^32 / d) (0xFFFFFFFF for d = 1): the estimate
+// mulhi(n, magic) is the quotient or one less, so one correction step makes it exact.  Six VALU
+// instructions instead of the ~35 of a generic 32-bit division; every VALU instruction stalls the matrix
+// pipe of its SIMD, so the prologue and epilogue arithmetic is kept short too.
+__device__ inline void fast_divmod(int n, int d, unsigned magic, int &q, int &r)
+{
+    q = (int)__umulhi((unsigned)n, magic);
+    r = n - q * d;
+    const int adj = r >= d;
+    q += adj;
+    r -= adj ? d : 0;
 }
 
 // Hardware deals workgroup i to XCD i % 8.  Returns a logical tile index such that the
@@ -127,23 +143,28 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
     if (a.c_split == 1 || a.partial != nullptr) {
         // A lane holds one pixel and 4 consecutive channels per register quad: one 16-byte store each.
         // With a workspace, split s stores its partial tile into plane s; a second kernel adds the planes.
+        // Buffer stores: the per-lane part of the address (pixel, channel quad) is computed once per pixel
+        // tile, the channel-block part is a scalar offset, and lanes past the end of the tensor get an
+        // out-of-range offset, which drops their store.
         float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
+        const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, a.out_bytes);
+        const int kb_stride = a.PQ * 64;  // bytes from one 16-channel block plane to the next
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int m = m0 + (wm * TM + tm) * 32 + l32;
-            if (m >= a.M) continue;
-            const int n = m / a.PQ;
-            const int pq = m - n * a.PQ;
+            int n, pq;
+            fast_divmod(m, a.PQ, a.magic_pq, n, pq);
+            const unsigned voff = m < a.M ? (unsigned)((n * a.Kb * a.PQ + pq) * 64 + half * 16) : kOobOffset;
 #pragma unroll
             for (int tk = 0; tk < TK; ++tk) {
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
-                    const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8 + half * 4;
-                    if (ofm >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
-                    float *o = base + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
+                    const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8;  // uniform; this lane: + half*4
+                    if (ofm0 >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
                     const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
                                        acc[tk][tm][rq * 4 + 3]};
-                    *reinterpret_cast<floatx4 *>(o) = v;
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff,
+                                                           (ofm0 >> 4) * kb_stride + (ofm0 & 15) * 4, 0);
                 }
             }
         }
@@ -173,8 +194,8 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
                 const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + pr * EPITCH + c4 * 4);
                 const int m = m0 + (wm * TM + tm) * 32 + pr;
                 if (m < a.M && ofm < a.Kb * 16) {
-                    const int n = m / a.PQ;
-                    const int pq = m - n * a.PQ;
+                    int n, pq;
+                    fast_divmod(m, a.PQ, a.magic_pq, n, pq);
                     float *o = a.out + (((size_t)(n * a.Kb + (ofm >> 4))) * a.PQ + pq) * 16 + (ofm & 15);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) atomicAdd(o + e, v[e]);
@@ -294,10 +315,9 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         const int grp = i * NW + wave;
         const int m = m0 + grp * 16 + (lane >> 2);
         if (grp < Sh::PGRP && m < a.M) {
-            const int n = m / a.PQ;
-            const int pq = m - n * a.PQ;
-            const int p = pq / a.Q;
-            const int q = pq - p * a.Q;
+            int n, pq, p, q;
+            fast_divmod(m, a.PQ, a.magic_pq, n, pq);
+            fast_divmod(pq, a.Q, a.magic_q, p, q);
             h0[i] = p * a.stride - a.pad;
             w0[i] = q * a.stride - a.pad;
             poff[i] = (n * a.Cb * a.H + h0[i]) * a.W + w0[i];
