@@ -51,7 +51,7 @@ const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 }
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes;
+    int kt, mt, ring, threads, lds_bytes, group;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -59,7 +59,7 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     int n = 0;
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     n = n < cap ? n : cap;
-    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes};
+    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group};
     return n;
 }
 

@@ -42,9 +42,45 @@ struct Bf16Shape {
     static_assert((D - 2) * LPS <= 63, "vmcnt range");
 };
 
-template <int KT, int MT, int WK, int WM, int NBUF, int G>
+// Loads of ring-slot iteration `it` (counted from the start of the current unrolled block, whose first batch
+// element is e0 and first c-block cb0) for the baked-filter path: taps and c-block increments are compile-time
+// after unrolling, per-lane offsets come precomputed per tap, the rest is scalar arithmetic.
+template <class Sh, int NBUF, int G, int NTAP, int APW, int WPW>
+__device__ __forceinline__ void issue_baked_bf16(const ConvArgs &a, char *lds, const unsigned (&vtap)[APW][NTAP],
+                                                 const int (&wsoff)[WPW], const bool (&wok)[WPW],
+                                                 const unsigned (&vw)[WPW], int wave, int slot, int it, int e0, int cb0)
+{
+    constexpr int NW = Sh::NW;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int ee = it * G + g;
+        const int tap = ee % NTAP, cbi = ee / NTAP;
+        const bool valid = e0 + ee < a.nb_split;  // beyond the range: descriptors of size 0 read zeros
+        const __amdgpu_buffer_rsrc_t rin_v = make_rsrc(a.in, valid ? a.in_bytes : 0u);
+        const int soff = (cb0 + cbi) * a.plane_bytes;
+        char *abase = lds + slot * Sh::SLOT + g * Sh::A_EL;
+        char *wbase = lds + slot * Sh::SLOT + G * Sh::A_EL + g * Sh::W_EL;
+#pragma unroll
+        for (int i = 0; i < APW; ++i) {
+            const int grp = i * NW + wave;
+            char *dst = (Sh::PGRP % NW == 0 || grp < Sh::PGRP) ? abase + grp * 1024 : lds + NBUF * Sh::SLOT;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rin_v, (lds_ptr_t)dst, 16, vtap[i][tap], soff, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WPW; ++i) {
+            const int pair = i * NW + wave;
+            const __amdgpu_buffer_rsrc_t rwt_v = make_rsrc(a.wt, (valid & wok[i]) ? a.wt_bytes : 0u);
+            char *dst = (Sh::WINS % NW == 0 || pair < Sh::WINS) ? wbase + pair * 1024 : lds + NBUF * Sh::SLOT;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt_v, (lds_ptr_t)dst, 16, vw[i], wsoff[i] + ((e0 + ee) << 9), 0, 0);
+        }
+    }
+}
+
+// SIDE > 0: R = S = SIDE baked into the loop (see the fp32 kernel): no vector-ALU work per load.
+template <int KT, int MT, int WK, int WM, int NBUF, int G, int SIDE>
 __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvArgs a)
 {
+    constexpr int TAPS = SIDE * SIDE;
     using Sh = Bf16Shape<KT, MT, WK, WM, NBUF, G>;
     constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
     constexpr int APW = Sh::APW, WPW = Sh::WPW, LPS = Sh::LPS, D = Sh::D;
@@ -124,6 +160,30 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
         }
     };
 
+    // ---- loader of the baked-filter path: offsets per tap, validity folded in ---------------------
+    constexpr int NTAP = TAPS > 0 ? TAPS : 1;
+    unsigned vtap[APW][NTAP], vw[WPW];
+    int wsoff[WPW];
+    bool wok[WPW];
+    if constexpr (TAPS > 0) {
+#pragma unroll
+        for (int i = 0; i < APW; ++i)
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t) {
+                const int r = t / SIDE, sx = t % SIDE;
+                const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W);
+                vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 32 + (lane & 1) * 16) : kOobOffset;
+            }
+#pragma unroll
+        for (int i = 0; i < WPW; ++i) {
+            const int pair = i * NW + wave;
+            wok[i] = Sh::WINS % NW == 0 || pair < Sh::WINS;
+            wsoff[i] = ((kb0 + 2 * pair) * a.NB + b_begin) << 9;
+            // lanes 32..63 fetch the next filter block (NB blocks further on), if it exists
+            vw[i] = kb0 + 2 * pair + half < a.Kb ? (unsigned)(half * a.NB * 512 + l32 * 16) : kOobOffset;
+        }
+    }
+
     // ---- reader bookkeeping -------------------------------------------------------------------
     int paddr[TM], waddr[TK];
 #pragma unroll
@@ -168,18 +228,47 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
 
     // ---- pipeline over ring slots of G batch elements (range padded with zero elements) -----------
     const int nslot = (a.nb_split + G - 1) / G;
+    if constexpr (TAPS > 0) {
+        // unrolled so that ring slot, fragment parity and the taps of every element are static
+        constexpr int TG = TAPS / ct_gcd(TAPS, G);
+        constexpr int U = NBUF / ct_gcd(NBUF, TG) * TG;  // iterations per unrolled block; U * G is a multiple of TAPS
+        int cb0 = b_begin / TAPS;
 #pragma unroll
-    for (int e = 0; e < D; ++e) issue_loads(e);
-    wait_vm_and_barrier<(D - 1) * LPS>();
-    read_frags(0, 0);
-    for (int s0 = 0; s0 < nslot; s0 += NBUF) {
+        for (int e = 0; e < D; ++e)
+            issue_baked_bf16<Sh, NBUF, G, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+        wait_vm_and_barrier<(D - 1) * LPS>();
+        read_frags(0, 0);
+        for (int s0 = 0; s0 < nslot; s0 += U, cb0 += U * G / TAPS) {
 #pragma unroll
-        for (int u = 0; u < NBUF; ++u) {
-            wait_vm_and_barrier<(D - 2) * LPS>();
-            read_frags((u + 1) % NBUF, (u + 1) % 2);
-            issue_loads(u % NBUF);
-            mfmas(u % 2);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int u = 0; u < U; ++u) {
+                wait_vm_and_barrier<(D - 2) * LPS>();
+                read_frags((u + 1) % NBUF, (u + 1) % 2);
+                issue_baked_bf16<Sh, NBUF, G, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,
+                                                              s0 * G, cb0);
+                mfmas(u % 2);
+#pragma unroll
+                for (int i = 0; i < TK * TM * G; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < D; ++e) issue_loads(e);
+        wait_vm_and_barrier<(D - 1) * LPS>();
+        read_frags(0, 0);
+        for (int s0 = 0; s0 < nslot; s0 += NBUF) {
+#pragma unroll
+            for (int u = 0; u < NBUF; ++u) {
+                wait_vm_and_barrier<(D - 2) * LPS>();
+                read_frags((u + 1) % NBUF, (u + 1) % 2);
+                issue_loads(u % NBUF);
+                mfmas(u % 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -187,15 +276,17 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
     write_out<KT, TK, TM, WK, Sh::EPITCH>(a, tc, acc, lds, m0, wave, lane);
 }
 
-template <int KT, int MT, int WK, int WM, int NBUF, int G>
+template <int KT, int MT, int WK, int WM, int NBUF, int G, int SIDE>
 void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((conv_fwd_bf16_kernel<KT, MT, WK, WM, NBUF, G>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
+    hipLaunchKernelGGL((conv_fwd_bf16_kernel<KT, MT, WK, WM, NBUF, G, SIDE>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
 
+// G batch elements per iteration; the 3x3-baked kernels take one filter row (3 elements) per iteration
 #define PS_BF16_SHAPE(KT, MT, WK, WM, NBUF, G)                                                          \
-    {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES,                 \
-     &launch_bf16<KT, MT, WK, WM, NBUF, G>, nullptr, nullptr, nullptr}
+    {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES, G,              \
+     &launch_bf16<KT, MT, WK, WM, NBUF, G, 0>, &launch_bf16<KT, MT, WK, WM, NBUF, G, 1>,                 \
+     &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, nullptr}
 #define PS_BF16_RINGS(KT, MT, WK, WM, G) PS_BF16_SHAPE(KT, MT, WK, WM, 2, G), PS_BF16_SHAPE(KT, MT, WK, WM, 4, G)
 
 //                 KT   MT  WK WM  G        wave tile (channels x pixels)

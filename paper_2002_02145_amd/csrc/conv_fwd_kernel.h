@@ -506,6 +506,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 typedef void (*LaunchFn)(const ConvArgs &, unsigned grid, hipStream_t);
 struct ShapeEntry {
     int dtype, kt, mt, ring, threads, lds_bytes;
+    int group;            // batch elements per loop iteration of the general kernel (fp32: 1)
     LaunchFn launch;      // any filter size
     LaunchFn launch_1x1;  // R = S = 1 baked in (nullptr if not compiled)
     LaunchFn launch_3x3;  // R = S = 3 baked in
@@ -519,7 +520,7 @@ void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
 }
 
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
-    {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES,                      \
+    {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES, 1,                   \
      &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
      &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32<KT, MT, WK, WM, NBUF, 7>}
 

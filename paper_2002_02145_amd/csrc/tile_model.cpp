@@ -22,7 +22,7 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes;
+    int kt, mt, ring, threads, lds_bytes, group;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
 
@@ -42,11 +42,13 @@ struct Chip {
     double l2_bw = 14.0e12;                   // L2 -> LDS, all XCDs
     double atomic_bw = 0.35e12;               // fp32 atomic adds (resolved memory-side across XCDs), payload bytes/s
     double mfma_flop_clk_cu[2] = {256.0, 4096.0};  // f32, bf16
-    double steady_eff = 0.84;                 // matrix-core issue efficiency of the general loop (VALU address work)
+    double steady_eff_general[2] = {0.84, 0.45};  // matrix-core issue efficiency of the general loop (VALU address work)
     double steady_eff_baked = 0.97;           // ... of the loops with a baked filter size (no VALU work)
     double load_latency_clk = 1150.0;         // global load to LDS, L2 hit under load
     double fill_clk = 4500.0;                 // first loads of a workgroup (nothing to overlap with)
     double launch_us = 1.5;
+    double dependent_launch_us = 3.5;         // a kernel that has to wait for the previous one to drain
+    double reduce_ineff = 1.4;                // the plane-adding pass against streaming bandwidth
 };
 
 const Chip kChip;
@@ -56,16 +58,29 @@ const Chip kChip;
 bool baked_filter(const Dims &dm, int nb_split)
 {
     if (packs_taps(dm)) return nb_split == dm.NB;  // unsplit only
-    return dm.dtype == PS_F32 && dm.R == dm.S && (dm.R == 1 || dm.R == 3) && nb_split % (dm.R * dm.S) == 0;
+    return dm.R == dm.S && (dm.R == 1 || dm.R == 3) && nb_split % (dm.R * dm.S) == 0;
+}
+
+// batch elements one loop iteration of the kernel consumes (the 16-bit kernels group several per ring slot;
+// their 3x3 variant takes one filter row)
+int group_of(const Dims &dm, const ShapeInfo &sh, int nb_split)
+{
+    if (dm.dtype == PS_F32) return 1;
+    return baked_filter(dm, nb_split) && dm.R == 3 ? 3 : sh.group;
 }
 
 // batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples
 int logical_elems(const Dims &dm, int nb_split) { return baked_filter(dm, nb_split) && packs_taps(dm) ? 14 : nb_split; }
 
-int padded_elems(const Dims &dm, int ring, int nb_split)
+int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
 {
+    const int ring = sh.ring;
     int unit = ring;
-    if (baked_filter(dm, nb_split)) {
+    if (dm.dtype != PS_F32) {
+        const int g = group_of(dm, sh, nb_split);
+        unit = ring * g;
+        if (g == 3) unit = ring % 3 == 0 ? ring * 3 : ring * 9;  // lcm(ring, 3) iterations of 3 elements
+    } else if (baked_filter(dm, nb_split)) {
         const int taps = packs_taps(dm) ? 14 : dm.R * dm.S;
         if (packs_taps(dm)) nb_split = 14;  // 7 rows x 2 groups of 4 taps replace the 49 taps
         int g = ring, h = taps;
@@ -88,7 +103,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double n_mt = std::ceil(M / t.mt), n_kt = std::ceil((double)dm.K / t.kt);
     const double nwg = n_mt * n_kt * t.c_split;
     const double nb_split = (double)dm.NB / t.c_split;
-    const double nb_pad = padded_elems(dm, t.ring, dm.NB / t.c_split);  // zero elements pad the range
+    const double nb_pad = padded_elems(dm, sh, dm.NB / t.c_split);  // zero elements pad the range
     const bool baked = baked_filter(dm, dm.NB / t.c_split);
     const double es = dm.es;
     const double waves_wg = sh.threads / 64.0;
@@ -106,18 +121,20 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double per_cu = std::ceil(nwg / c.cus);
     const double per_simd = std::ceil(per_cu * waves_wg / 4.0);
     const double mfma_clk = dm.dtype == PS_F32 ? 64.0 * 8.0 : 32.0;  // per 32x32 tile per batch element
-    const double eff = baked ? c.steady_eff_baked : c.steady_eff;
+    const double eff = baked ? c.steady_eff_baked : c.steady_eff_general[dm.dtype == PS_F32 ? 0 : 1];
     const double clk_wave = tiles_wave * mfma_clk * nb_pad / eff;
     // per batch element a wave also pays a barrier and the issue of its loads and LDS reads; with a
     // single resident wave per SIMD nothing hides that
     const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
-    double clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * nb_pad;
+    const double grp = group_of(dm, sh, dm.NB / t.c_split);  // batch elements per loop iteration
+    const double n_iter = nb_pad / grp;
+    double clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * n_iter;
     // a load issued in iteration b must have landed (ring - 1) iterations later: the part of the latency
     // the ring does not cover stalls every wave of the SIMD, and latency varies, so a thin margin still costs
-    const double clk_iter = tiles_wave * mfma_clk / eff * waves_res;  // wall clock of one iteration
+    const double clk_iter = tiles_wave * mfma_clk * grp / eff * waves_res;  // wall clock of one iteration
     const double cover = (t.ring - 1) * clk_iter / c.load_latency_clk;
     const double stall = std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) + 0.50 * clk_iter * std::exp(-cover);
-    clk_iter_overhead += stall * nb_pad / waves_res;
+    clk_iter_overhead += stall * n_iter / waves_res;
     const double clk_epi = tiles_wave * (t.c_split > 1 && !with_ws ? 900.0 : 250.0);
     const double rounds = std::ceil(per_cu / occ);
     const double t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk +
@@ -152,7 +169,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         t_extra = out_bytes / c.hbm_bw * 1e6 + c.launch_us;  // the clearing pass
     } else if (t.c_split > 1) {
         t_mem += out_bytes * t.c_split / far_bw;  // partial planes written once ...
-        t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 + c.launch_us;  // ... and added by a second pass
+        t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 * c.reduce_ineff + c.dependent_launch_us;  // ... and added by a second pass
     }
     return (std::max(t_mfma, t_mem) + 0.12 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us + t_extra;
 }
@@ -182,10 +199,10 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
             int shallowest = 1 << 30;
             for (int j = 0; j < ns; ++j)
                 if (shapes[j].kt == s.kt && shapes[j].mt == s.mt) {
-                    if (padded_elems(dm, shapes[j].ring, nbs) == logical_elems(dm, nbs)) any_exact = true;
+                    if (padded_elems(dm, shapes[j], nbs) == logical_elems(dm, nbs)) any_exact = true;
                     shallowest = std::min(shallowest, shapes[j].ring);
                 }
-            const bool exact = padded_elems(dm, s.ring, nbs) == logical_elems(dm, nbs);
+            const bool exact = padded_elems(dm, s, nbs) == logical_elems(dm, nbs);
             if (any_exact ? !exact : s.ring != shallowest) continue;
             if (sp > 1 && base_wg * sp > 8 * 256) continue;  // split only under-filled grids
             for (int raster = 0; raster < 2; ++raster) {
