@@ -19,10 +19,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 
-def kernel_source_digest() -> str:
-    """Digest of the sources that decide what the convolution kernels do and which tile runs."""
+def kernel_source_digest(dtype: str = "f32") -> str:
+    """Digest of the sources that decide what the convolution kernel of `dtype` ("f32" or "bf16") does."""
     h = hashlib.sha256()
-    for f in ("conv_fwd_kernel.h", "conv_fwd_f32.hip", "conv_fwd_bf16.hip", "tile_model.cpp", "api.hip"):
+    for f in ("conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip", "api.hip"):
         with open(os.path.join(HERE, "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
@@ -57,6 +57,7 @@ def main(argv=None) -> int:
     ap.add_argument("dir")
     ap.add_argument("--ref-copy-mib", type=int, default=256)
     ap.add_argument("--kernel", default="conv_fwd", help="substring of the kernel of interest")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="which kernel sources the digest covers")
     a = ap.parse_args(argv)
     out = []
     stats = _one(os.path.join(a.dir, "trace", "*kernel_stats.csv"))
@@ -104,8 +105,8 @@ def main(argv=None) -> int:
         tot = sum(traffic.values())
         out.append(f"HBM-side traffic of {a.kernel} per launch: fetch {traffic.get('FETCH_SIZE', 0) / 1e6:.2f} MB + "
                    f"write {traffic.get('WRITE_SIZE', 0) / 1e6:.2f} MB = {tot / 1e6:.2f} MB")
-        out.append(f"kernel source digest: {kernel_source_digest()}")
-        out.append(f"bench.py constant: ({kernel_source_digest()!r}, {int(tot)})")
+        out.append(f"kernel source digest ({a.dtype}): {kernel_source_digest(a.dtype)}")
+        out.append(f"bench.py constant: ({kernel_source_digest(a.dtype)!r}, <tile the trace names>, {int(tot)})")
     print("\n".join(out))
     return 0
 
