@@ -38,6 +38,31 @@ class Tile(ctypes.Structure):
         return f"Tile(kt={self.kt}, mt={self.mt}, ring={self.ring}, c_split={self.c_split}, raster={self.raster})"
 
 
+class LoopNest(ctypes.Structure):
+    _fields_ = [("n_loops", ctypes.c_int32), ("extent", ctypes.c_int32 * 8)]
+
+
+class ArrayRef(ctypes.Structure):
+    """array[f_0][f_1]..., f_d = sum_l coef[d][l] * iter_l + offset[d]."""
+    _fields_ = [("array", ctypes.c_int32), ("n_dims", ctypes.c_int32), ("is_write", ctypes.c_int32),
+                ("elem_bytes", ctypes.c_int32), ("coef", (ctypes.c_int32 * 8) * 4), ("offset", ctypes.c_int32 * 4)]
+
+    @classmethod
+    def of(cls, array: int, coef, offset=None, is_write: bool = False, elem_bytes: int = 1):
+        r = cls()
+        r.array, r.n_dims, r.is_write, r.elem_bytes = array, len(coef), int(is_write), elem_bytes
+        for d, row in enumerate(coef):
+            for l, c in enumerate(row):
+                r.coef[d][l] = c
+            r.offset[d] = 0 if offset is None else offset[d]
+        return r
+
+
+class ReuseDep(ctypes.Structure):
+    _fields_ = [("src_ref", ctypes.c_int32), ("tgt_ref", ctypes.c_int32), ("ws_min", ctypes.c_int64),
+                ("ws_max", ctypes.c_int64)]
+
+
 class PsError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
@@ -76,6 +101,12 @@ def _load() -> ctypes.CDLL:
         "ps_tile_cost_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select": (ctypes.c_int, [dp, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+        "ps_reuse_working_sets": (ctypes.c_int, [ctypes.POINTER(LoopNest), ctypes.POINTER(ArrayRef), ctypes.c_int,
+                                                 ctypes.POINTER(ReuseDep), ctypes.c_int]),
+        "ps_reuse_assign": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
+        "ps_reuse_cost": (ctypes.c_double, [ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_int64,
+                                            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -200,3 +231,43 @@ def ps_tile_select(desc: ConvDesc) -> tuple[Tile, float]:
     t, us = Tile(), ctypes.c_double()
     _check(lib.ps_tile_select(ctypes.byref(desc), ctypes.byref(t), ctypes.byref(us)), "ps_tile_select")
     return t, us.value
+
+
+def ps_reuse_working_sets(extents, refs) -> list[tuple[int, int, int, int]]:
+    """Algorithm 1 on a rectangular nest: [(src_ref, tgt_ref, ws_min, ws_max), ...] for every dependence."""
+    nest = LoopNest()
+    nest.n_loops = len(extents)
+    for l, e in enumerate(extents):
+        nest.extent[l] = e
+    arr = (ArrayRef * len(refs))(*refs)
+    n = lib.ps_reuse_working_sets(ctypes.byref(nest), arr, len(refs), None, 0)
+    if n < 0:
+        raise PsError(n, "ps_reuse_working_sets")
+    out = (ReuseDep * max(n, 1))()
+    n = lib.ps_reuse_working_sets(ctypes.byref(nest), arr, len(refs), out, n)
+    if n < 0:
+        raise PsError(n, "ps_reuse_working_sets")
+    return [(out[i].src_ref, out[i].tgt_ref, out[i].ws_min, out[i].ws_max) for i in range(n)]
+
+
+def ps_reuse_assign(ws, cache_sizes) -> tuple[list[int], int]:
+    """Algorithm 2: ([WS per cache level], WS served from memory)."""
+    ws, cache_sizes = list(ws), list(cache_sizes)
+    w = (ctypes.c_int64 * max(len(ws), 1))(*ws)
+    c = (ctypes.c_int64 * max(len(cache_sizes), 1))(*cache_sizes)
+    lvl = (ctypes.c_int64 * max(len(cache_sizes), 1))()
+    mem = ctypes.c_int64()
+    _check(lib.ps_reuse_assign(w, len(ws), c, len(cache_sizes), lvl, ctypes.byref(mem)), "ps_reuse_assign")
+    return [lvl[i] for i in range(len(cache_sizes))], mem.value
+
+
+def ps_reuse_cost(level_ws, mem_ws: int, lat, bw) -> float:
+    """Eq. 1; lat and bw carry one entry per cache level and a last one for memory."""
+    n = len(level_ws)
+    if len(lat) != n + 1 or len(bw) != n + 1:
+        raise PsError(PS_EINVAL, "ps_reuse_cost")
+    c = lib.ps_reuse_cost((ctypes.c_int64 * max(n, 1))(*level_ws), n, int(mem_ws),
+                          (ctypes.c_double * (n + 1))(*lat), (ctypes.c_double * (n + 1))(*bw))
+    if c < 0:
+        raise PsError(PS_EINVAL, "ps_reuse_cost")
+    return c
