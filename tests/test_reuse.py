@@ -93,3 +93,28 @@ def test_library_rejects_bad_arguments(ps):
         ps.ps_reuse_working_sets((4096, 4096, 4096), _to_lib(ps, ro.matmul_refs()))   # too many iterations
     with pytest.raises(ps.PsError):
         ps.ps_reuse_cost([1], 1, [1.0, 1.0], [1.0, 0.0])
+
+
+def test_rank_report_on_a_synthetic_sweep(ps, tmp_path):
+    """The report runs on the host from a sweep file; times here are made up (the tile model's own cost plus a
+    deterministic wobble), so only the mechanics are checked."""
+    import io
+    import json
+    from paper_2002_02145_amd import rank_report, workloads as wl
+    L = wl.resnet50_layers()[5]                      # a 1x1 layer
+    d = ps.ConvDesc.of(L)
+    rows = []
+    for i in range(ps.ps_tile_count(d)):
+        t = ps.ps_tile_get(d, i)
+        rows.append({"tile": list(t.as_tuple()), "us": ps.ps_tile_cost_ws_us(d, t) * (1.0 + 0.03 * ((i * 7) % 5))})
+    f = tmp_path / "sweep.jsonl"
+    f.write_text(json.dumps({"layer": L.name, "split_reduction": "workspace", "rows": rows}) + "\n")
+    out = io.StringIO()
+    s = rank_report.report(str(f), "f32", True, out)
+    assert s["layers"] == 1 and 0.0 <= s["worst_top5_loss"] <= s["worst_top1_loss"] <= 0.13
+    row = json.loads(out.getvalue().splitlines()[0])
+    assert row["eq1_candidates"] == len(rows) and -1.0 <= row["eq1_spearman"] <= 1.0
+    # Eq. 1 prefers fewer bytes through the slow levels: a larger tile of the same shape family never costs more
+    small = rank_report.paper_cost(L, 4, (64, 64, 4, 1, 0))
+    large = rank_report.paper_cost(L, 4, (64, 128, 4, 1, 0))
+    assert small is not None and large is not None and small > 0 and large > 0
