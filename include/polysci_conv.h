@@ -109,6 +109,25 @@ size_t ps_workspace_bytes(const ps_conv_desc *d, const ps_tile *t); /* c_split *
 int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
                      void *out_blk, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Convolution with the work of the following layers of an inference pipeline fused into the store of the output
+ * tile (Section 5 evaluates the convolutions of such pipelines; what follows each one there is a bias, an activation
+ * and the next convolution).  y = conv(in, wt) as above, then in this order:
+ *   bias      != NULL: y[n][k][p][q] += bias[k]   (device pointer to K fp32 values, 16-byte aligned)
+ *   relu      != 0   : y = max(y, 0)
+ *   out_dtype        : PS_F32 stores y as ps_conv2d_fwd does; PS_BF16 rounds y to bf16 (nearest, ties to even) and
+ *                      stores [N][Kb][P][Q][16 k] with 2-byte elements (N*K*P*Q*2 bytes).
+ * Either way out_blk has exactly the blocked activation layout of a next layer with C = K, H = P, W = Q of that
+ * element type, so layers chain with no transform in between.  Tile and workspace as for ps_conv2d_fwd_ws; a tile
+ * with c_split > 1 needs its workspace (PS_EINVAL without), because the epilogue is applied where the sum is
+ * complete. */
+typedef struct {
+    const void *bias;
+    int32_t relu;
+    int32_t out_dtype; /* ps_dtype */
+} ps_epilogue;
+int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, const ps_epilogue *e, const void *in_blk,
+                        const void *wt_blk, void *out_blk, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- outer-loop variant space and its ranking (Section 4.2, Algorithm 2, Eq. 1) ------- */
 /* Number of candidate tiles the enumerator emits for `d` (negative ps_status on error). */
 int ps_tile_count(const ps_conv_desc *d);

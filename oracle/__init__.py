@@ -130,3 +130,28 @@ def normalised_error(got: np.ndarray, out: np.ndarray, mag: np.ndarray) -> float
     if np.all(zero):
         return 0.0
     return float(np.max(diff[~zero] / mag[~zero]))
+
+
+def round_to_bf16(y: np.ndarray) -> np.ndarray:
+    """Finite float64 values rounded to the nearest bfloat16 (8 significant bits), ties to even; result as float64."""
+    y = np.asarray(y, dtype=np.float64)
+    m, e = np.frexp(y)                       # y = m * 2**e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0), e - 8)   # np.rint rounds half to even
+
+
+def conv2d_fwd_fused(shape, x: np.ndarray, w: np.ndarray, bias: np.ndarray | None = None, relu: bool = False,
+                     out_bf16: bool = False):
+    """What follows a convolution in an inference pipeline, applied to the exact result in this order:
+    per-output-channel bias, max(., 0), rounding of the output to bfloat16.  Returns (y, mag, y_before_rounding)
+    with mag = sum |x*w| + |bias|, the scale the accumulation error is measured against."""
+    out, mag = conv2d_fwd(shape, x, w)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64).reshape(1, -1, 1, 1)
+        out = out + b
+        mag = mag + np.abs(b)
+    if relu:
+        out = np.maximum(out, 0.0)
+    exact = out
+    if out_bf16:
+        out = round_to_bf16(out)
+    return out, mag, exact

@@ -63,6 +63,10 @@ class ReuseDep(ctypes.Structure):
                 ("ws_max", ctypes.c_int64)]
 
 
+class Epilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("relu", ctypes.c_int32), ("out_dtype", ctypes.c_int32)]
+
+
 class PsError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
@@ -93,6 +97,7 @@ def _load() -> ctypes.CDLL:
         "ps_conv2d_fwd_tile": (ctypes.c_int, [dp, tp, vp, vp, vp, vp]),
         "ps_workspace_bytes": (ctypes.c_size_t, [dp, tp]),
         "ps_conv2d_fwd_ws": (ctypes.c_int, [dp, tp, vp, vp, vp, vp, ctypes.c_size_t, vp]),
+        "ps_conv2d_fwd_fused": (ctypes.c_int, [dp, tp, ctypes.POINTER(Epilogue), vp, vp, vp, vp, ctypes.c_size_t, vp]),
         "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_tile_count": (ctypes.c_int, [dp]),
@@ -193,6 +198,14 @@ def ps_conv2d_fwd_ws(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace, w
     tp = ctypes.byref(tile) if tile is not None else None
     _check(lib.ps_conv2d_fwd_ws(ctypes.byref(desc), tp, _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk),
                                 _ptr(workspace), int(workspace_bytes), _stream(stream)), "ps_conv2d_fwd_ws")
+
+
+def ps_conv2d_fwd_fused(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace=None, workspace_bytes: int = 0,
+                        bias=None, relu: bool = False, out_dtype: int = PS_F32, stream=None) -> None:
+    e = Epilogue(_ptr(bias) or None, int(relu), int(out_dtype))
+    tp = ctypes.byref(tile) if tile is not None else None
+    _check(lib.ps_conv2d_fwd_fused(ctypes.byref(desc), tp, ctypes.byref(e), _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk),
+                                   _ptr(workspace) or None, int(workspace_bytes), _stream(stream)), "ps_conv2d_fwd_fused")
 
 
 def ps_tile_cost_ws_us(desc: ConvDesc, tile: Tile) -> float:

@@ -76,13 +76,15 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     return PS_OK;
 }
 
-int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, float *ws, hipStream_t st)
+int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, float *ws, hipStream_t st,
+                const float *bias = nullptr, int epi = 0)
 {
     int rc = tile_valid(dm, t);
     if (rc != PS_OK) return rc;
     const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.ring);
     ConvArgs a;
     a.in = in; a.wt = wt; a.out = out;
+    a.bias = bias; a.epi = epi;
     a.H = dm.H; a.W = dm.W; a.Cb = dm.Cb; a.Kb = dm.Kb; a.R = dm.R; a.S = dm.S;
     a.stride = dm.stride; a.pad = dm.pad; a.Q = dm.Q;
     a.PQ = dm.P * dm.Q;
@@ -118,7 +120,8 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     fn(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
     rc = hip_status(hipGetLastError());
     if (rc != PS_OK) return rc;
-    if (t.c_split > 1 && ws) rc = launch_reduce_planes(ws, out, (size_t)dm.M * dm.K, t.c_split, st);
+    if (t.c_split > 1 && ws)
+        rc = launch_reduce_planes(ws, out, (size_t)dm.M * dm.K, t.c_split, bias, epi, dm.P * dm.Q, dm.Kb, st);
     return rc;
 }
 
@@ -207,6 +210,34 @@ extern "C" int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const v
     if (need > 0 && (!workspace || workspace_bytes < need)) return PS_EINVAL;
     return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr,
                        (hipStream_t)stream);
+}
+
+extern "C" int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, const ps_epilogue *e, const void *in_blk,
+                                   const void *wt_blk, void *out_blk, void *workspace, size_t workspace_bytes,
+                                   void *stream)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!e || !in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (e->out_dtype != PS_F32 && e->out_dtype != PS_BF16) return PS_EUNSUPPORTED;
+    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk) || !aligned16(workspace) || !aligned16(e->bias))
+        return PS_EINVAL;
+    ps_tile pick;
+    if (!t) {
+        double us;
+        rc = ps_tile_select_ws(d, workspace ? workspace_bytes : 0, &pick, &us);
+        if (rc != PS_OK) return rc;
+        t = &pick;
+    }
+    rc = tile_valid(dm, *t);
+    if (rc != PS_OK) return rc;
+    // a split reduction can only apply the epilogue where the sum is complete: in the plane-adding pass
+    const size_t need = t->c_split > 1 ? (size_t)t->c_split * (size_t)dm.M * dm.K * 4 : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PS_EINVAL;
+    const int epi = (e->bias ? 1 : 0) | (e->relu ? 2 : 0) | (e->out_dtype == PS_BF16 ? 4 : 0);
+    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr,
+                       (hipStream_t)stream, (const float *)e->bias, epi);
 }
 
 extern "C" int ps_tile_valid(const ps_conv_desc *d, const ps_tile *t)

@@ -43,22 +43,36 @@ int launch_fill_zero(float *p, size_t n, hipStream_t stream)
     return hip_status(hipGetLastError());
 }
 
-// out = sum over planes of partial[plane][.]; n4 = out elements / 4 (blocked outputs are multiples of 16).
-__global__ __launch_bounds__(256) void reduce_planes_kernel(const floatx4 *__restrict__ partial, floatx4 *__restrict__ out,
-                                                            size_t n4, int planes)
+// out = epilogue(sum over planes of partial[plane][.]); n4 = out elements / 4 (blocked outputs are multiples of 16).
+// The output is [N][Kb][PQ][16 k]: element e belongs to channel ((e / (16 * PQ)) % Kb) * 16 + e % 16.
+__global__ __launch_bounds__(256) void reduce_planes_kernel(const floatx4 *__restrict__ partial, void *__restrict__ out,
+                                                            size_t n4, int planes, const float *__restrict__ bias,
+                                                            int epi, unsigned pq4, int Kb)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n4) return;
     floatx4 s = partial[i];
     for (int p = 1; p < planes; ++p) s += partial[(size_t)p * n4 + i];
-    out[i] = s;
+    if (epi & 1) {
+        const int kb = (int)((i / pq4) % (unsigned)Kb);  // pq4 = 16 * PQ / 4 groups of four per channel-block plane
+        s += *reinterpret_cast<const floatx4 *>(bias + kb * 16 + (int)(i & 3) * 4);
+    }
+    if (epi & 2)
+        for (int k = 0; k < 4; ++k) s[k] = fmaxf(s[k], 0.f);
+    if (epi & 4) {
+        const uintx2_t h = {pack_bf16(s[0], s[1]), pack_bf16(s[2], s[3])};
+        reinterpret_cast<uintx2_t *>(out)[i] = h;
+    } else {
+        reinterpret_cast<floatx4 *>(out)[i] = s;
+    }
 }
 
-int launch_reduce_planes(const float *partial, float *out, size_t n, int planes, hipStream_t stream)
+int launch_reduce_planes(const float *partial, void *out, size_t n, int planes, const float *bias, int epi, int PQ, int Kb,
+                         hipStream_t stream)
 {
     const size_t n4 = n / 4;
     hipLaunchKernelGGL(reduce_planes_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
-                       reinterpret_cast<const floatx4 *>(partial), reinterpret_cast<floatx4 *>(out), n4, planes);
+                       reinterpret_cast<const floatx4 *>(partial), out, n4, planes, bias, epi, (unsigned)(4 * PQ), Kb);
     return hip_status(hipGetLastError());
 }
 

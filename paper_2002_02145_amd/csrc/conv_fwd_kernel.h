@@ -58,6 +58,8 @@ struct ConvArgs {
     int nb_split;  // batch elements per split
     int c_split;
     int n_mt, n_kt;
+    const float *bias;  // per output channel, added before the store (epi & 1)
+    int epi;            // fused epilogue: 1 = add bias, 2 = max(x, 0), 4 = store bf16 (round to nearest even)
     int raster;
     unsigned in_bytes, wt_bytes;
     int plane_bytes;       // bytes of one [H][W][16] c-block plane of the input
@@ -131,6 +133,17 @@ __device__ inline void wait_vm_and_barrier()
     asm volatile("" ::: "memory");
 }
 
+typedef unsigned uintx2_t __attribute__((ext_vector_type(2)));
+
+// Two finite fp32 values rounded to bf16 (nearest, ties to even), packed low | high << 16.
+__device__ inline unsigned pack_bf16(float lo, float hi)
+{
+    const unsigned a = __builtin_bit_cast(unsigned, lo), b = __builtin_bit_cast(unsigned, hi);
+    const unsigned ra = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
+    const unsigned rb = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+    return ra | rb;
+}
+
 // Epilogue shared by the fp32 and bf16 kernels: accumulators -> out[n][kb][p][q][16 k].
 // acc[tk][tm] is the 32x32 tile (output channels x pixels) number (tk, tm) of this wave in the MFMA
 // result layout: register r of lane l holds channel 8*(r/4) + 4*(l/32) + r%4 of pixel l%32.
@@ -147,24 +160,69 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
         // tile, the channel-block part is a scalar offset, and lanes past the end of the tensor get an
         // out-of-range offset, which drops their store.
         float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
-        const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, a.out_bytes);
-        const int kb_stride = a.PQ * 64;  // bytes from one 16-channel block plane to the next
+        const int epi = a.c_split == 1 ? a.epi : 0;  // a split's partial planes stay raw; the adding pass applies it
+        if (epi == 0) {
+            // plain store straight from the accumulator registers, which nothing overwrites afterwards
+            const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, a.out_bytes);
+            const int kb_stride = a.PQ * 64;  // bytes from one 16-channel block plane to the next
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int m = m0 + (wm * TM + tm) * 32 + l32;
+                int n, pq;
+                fast_divmod(m, a.PQ, a.magic_pq, n, pq);
+                const unsigned voff = m < a.M ? (unsigned)((n * a.Kb * a.PQ + pq) * 64 + half * 16) : kOobOffset;
+#pragma unroll
+                for (int tk = 0; tk < TK; ++tk) {
+#pragma unroll
+                    for (int rq = 0; rq < 4; ++rq) {
+                        const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8;  // uniform; this lane: + half*4
+                        if (ofm0 >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
+                        const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
+                                           acc[tk][tm][rq * 4 + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff,
+                                                               (ofm0 >> 4) * kb_stride + (ofm0 & 15) * 4, 0);
+                    }
+                }
+            }
+            return;
+        }
+        // Fused epilogue: bias, max(., 0), optional rounding to bf16.  The values pass through temporaries that the
+        // next quad's arithmetic reuses; a vector-ALU write to the data registers of a multi-dword store issued just
+        // before it can overtake the store's read of them on this hardware (the compiler only guards the form
+        // without a scalar offset).  The empty asm keeps the stored registers live across a short s_nop, so nothing
+        // can be scheduled or allocated into that window.
+        const bool bf16_out = epi & 4;
+        const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, bf16_out ? a.out_bytes / 2 : a.out_bytes);
+        const int esz = bf16_out ? 2 : 4;
+        const int kb_stride = a.PQ * 16 * esz;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int m = m0 + (wm * TM + tm) * 32 + l32;
             int n, pq;
             fast_divmod(m, a.PQ, a.magic_pq, n, pq);
-            const unsigned voff = m < a.M ? (unsigned)((n * a.Kb * a.PQ + pq) * 64 + half * 16) : kOobOffset;
+            const unsigned voff = m < a.M ? (unsigned)(((n * a.Kb * a.PQ + pq) * 16 + half * 4) * esz) : kOobOffset;
 #pragma unroll
             for (int tk = 0; tk < TK; ++tk) {
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
-                    const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8;  // uniform; this lane: + half*4
-                    if (ofm0 >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
-                    const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
-                                       acc[tk][tm][rq * 4 + 3]};
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff,
-                                                           (ofm0 >> 4) * kb_stride + (ofm0 & 15) * 4, 0);
+                    const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8;
+                    if (ofm0 >= a.Kb * 16) continue;
+                    floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
+                                 acc[tk][tm][rq * 4 + 3]};
+                    const int soff = (ofm0 >> 4) * kb_stride + (ofm0 & 15) * esz;
+                    if (epi & 1) v += *reinterpret_cast<const floatx4 *>(a.bias + ofm0 + half * 4);
+                    if (epi & 2) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+                    }
+                    if (bf16_out) {
+                        const uintx2_t h = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                        __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff, soff, 0);
+                        asm volatile("s_nop 1" ::"v"(h[0]), "v"(h[1]));
+                    } else {
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, 0);
+                        asm volatile("s_nop 1" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));
+                    }
                 }
             }
         }

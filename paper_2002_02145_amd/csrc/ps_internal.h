@@ -37,6 +37,7 @@ int conv_shape_lds_bytes(int dtype, int kt, int mt, int ring);
 int conv_shape_threads(int dtype, int kt, int mt, int ring);
 bool packs_taps(const Dims &dm);
 int launch_fill_zero(float *p, size_t n, hipStream_t stream);
-int launch_reduce_planes(const float *partial, float *out, size_t n, int planes, hipStream_t stream);
+int launch_reduce_planes(const float *partial, void *out, size_t n, int planes, const float *bias, int epi, int PQ, int Kb,
+                         hipStream_t stream);
 
 }  // namespace ps

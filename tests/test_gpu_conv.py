@@ -108,44 +108,18 @@ def test_full_size_configs_fp32(shape, seed):
 
 @pytest.mark.parametrize("dtype", [0, 1], ids=["fp32", "bf16"])
 def test_resnet50_sweep(dtype):
-    """Every layer of the ResNet-50-shaped sweep at N = 28 with the model's pick: one whole image plus
-    random samples of the rest.  bf16: inputs and filters rounded to bf16 first, oracle on the same values."""
+    """Every layer of the ResNet-50-shaped sweep at N = 28 with the model's pick, every output element against the
+    oracle (a fault that hits a few lanes of a few stores now and then does not show in one sampled image).
+    bf16: inputs and filters rounded to bf16 first, oracle on the same values."""
     from gpu_util import run_conv
     for i, shape in enumerate(wl.resnet50_layers()):
         x, w = _prep(shape, wl.relu_like, wl.sweep_seed(i), dtype)
         got = run_conv(shape, x, w, dtype, ws=True)      # the configuration bench.py times
-        n = i % shape.N
-        out, mag = oracle.conv2d_fwd(shape, x, w, images=(n, n + 1))
-        err = oracle.normalised_error(got[n:n + 1], out[n:n + 1], mag[n:n + 1])
+        out, mag = oracle.conv2d_fwd(shape, x, w)
+        err = oracle.normalised_error(got, out, mag)
         assert err <= TOL[dtype], f"{shape.name}: {err}"
         rng = np.random.default_rng(i)
-        for _ in range(100):
+        for _ in range(20):                              # the point-wise oracle agrees with the bulk one
             nn, k, p, q = (int(rng.integers(v)) for v in (shape.N, shape.K, shape.P, shape.Q))
             o, m = oracle.conv2d_fwd_point(shape, x, w, nn, k, p, q)
             assert abs(got[nn, k, p, q] - o) <= TOL[dtype] * m, shape.name
-
-
-def test_invalid_arguments_launch_nothing():
-    import torch
-    from paper_2002_02145_amd import binding as ps
-    d = ps.ConvDesc.of(wl.CFG1)
-    buf = torch.zeros(1 << 16, device="cuda:0")
-    with pytest.raises(ps.PsError) as e:
-        ps.ps_conv2d_fwd(d, 0, buf, buf)
-    assert e.value.status == ps.PS_EINVAL
-    bad_tile = ps.Tile(48, 128, 2, 1, 0)
-    with pytest.raises(ps.PsError) as e:
-        ps.ps_conv2d_fwd_tile(d, bad_tile, buf, buf, buf)
-    assert e.value.status == ps.PS_EUNSUPPORTED
-    with pytest.raises(ps.PsError) as e:
-        ps.ps_conv2d_fwd_tile(d, ps.Tile(64, 128, 2, 5, 0), buf, buf, buf)   # 36 batch elements % 5 != 0
-    assert e.value.status == ps.PS_EUNSUPPORTED
-    split = ps.Tile(64, 64, 2, 2, 0)
-    need = ps.ps_workspace_bytes(d, split)
-    assert need == 2 * 64 * 14 * 14 * 4
-    with pytest.raises(ps.PsError) as e:
-        ps.ps_conv2d_fwd_ws(d, split, buf, buf, buf, buf, need - 16)          # workspace too small
-    assert e.value.status == ps.PS_EINVAL
-    with pytest.raises(ps.PsError) as e:
-        ps.ps_conv2d_fwd_ws(d, split, buf, buf, buf, None, 0)
-    assert e.value.status == ps.PS_EINVAL

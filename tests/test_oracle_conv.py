@@ -231,3 +231,34 @@ def test_normalised_error_metric(oracle_lib):
     assert oracle_lib.normalised_error(np.array([1.0, 0.0, -2.0]), out, mag) == 0.0
     assert oracle_lib.normalised_error(np.array([1.5, 0.0, -2.0]), out, mag) == 0.25
     assert oracle_lib.normalised_error(np.array([1.0, 1e-30, -2.0]), out, mag) == float("inf")
+
+
+# ---- fused epilogue of the oracle (bias, max(., 0), bf16 rounding) ----------------------------------------------
+def test_round_to_bf16_matches_torch_and_known_ties(oracle_lib):
+    oracle = oracle_lib
+    import torch
+    rng = np.random.default_rng(3)
+    v = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-6, 6, 4000), [0.0, 1.0, -1.0, 255.0, 256.0]])
+    v32 = v.astype(np.float32)
+    want = torch.from_numpy(v32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oracle.round_to_bf16(v32.astype(np.float64)), want)
+    # ties go to the even 8-bit significand: 257 -> 256, 259 -> 260, 3 * 2**-9 + 1 -> 1 + 2**-7 ...
+    assert list(oracle.round_to_bf16(np.array([257.0, 259.0, 261.0, -257.0, 1.00390625, 1.01171875]))) == \
+        [256.0, 260.0, 260.0, -256.0, 1.0, 1.015625]
+
+
+def test_fused_epilogue_special_cases(oracle_lib):
+    oracle = oracle_lib
+    s = ConvShape(2, 5, 6, 7, 16, 3, 3, 1, 1)
+    x, w = uniform_pm1(s, 11)
+    bias = np.linspace(-1.0, 1.0, s.K).astype(np.float32)
+    plain, mag = oracle.conv2d_fwd(s, x, w)
+    y, m, _ = oracle.conv2d_fwd_fused(s, x, w, bias=bias)
+    assert np.allclose(y - plain, bias.reshape(1, -1, 1, 1), atol=1e-12) and np.all(m >= mag)
+    # zero filter: the output is the bias alone, and max(., 0) clips exactly its negative half
+    y0, _, _ = oracle.conv2d_fwd_fused(s, x, np.zeros_like(w), bias=bias, relu=True)
+    assert np.array_equal(y0, np.broadcast_to(np.maximum(bias, 0).astype(np.float64).reshape(1, -1, 1, 1), y0.shape))
+    yr, _, _ = oracle.conv2d_fwd_fused(s, x, w, relu=True)
+    assert np.array_equal(yr, np.maximum(plain, 0.0)) and yr.min() == 0.0
+    yb, _, exact = oracle.conv2d_fwd_fused(s, x, w, bias=bias, relu=True, out_bf16=True)
+    assert np.array_equal(yb, oracle.round_to_bf16(exact)) and np.all(np.abs(yb - exact) <= np.abs(exact) * 2.0 ** -8)
