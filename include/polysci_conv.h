@@ -146,6 +146,8 @@ int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us);
 int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *best, double *modelled_us);
 
 const char *ps_strerror(int status);
+/* The HIP runtime's description of the last PS_EHIP this thread received ("" if none); static storage. */
+const char *ps_last_hip_error(void);
 
 #ifdef __cplusplus
 }

@@ -78,6 +78,13 @@ def _load() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
             "There is no CPU fallback.")
+    # PyTorch ships a HIP runtime of its own.  Whichever copy is loaded first serves the whole process, and device
+    # pointers and streams only mean something to the runtime that made them, so torch (the source of both here) has
+    # to be loaded before the library binds to libamdhip64.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     dp = ctypes.POINTER(ConvDesc)
     tp = ctypes.POINTER(Tile)
@@ -106,6 +113,7 @@ def _load() -> ctypes.CDLL:
         "ps_tile_cost_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select": (ctypes.c_int, [dp, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+        "ps_last_hip_error": (ctypes.c_char_p, []),
         "ps_reuse_working_sets": (ctypes.c_int, [ctypes.POINTER(LoopNest), ctypes.POINTER(ArrayRef), ctypes.c_int,
                                                  ctypes.POINTER(ReuseDep), ctypes.c_int]),
         "ps_reuse_assign": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
@@ -123,7 +131,14 @@ lib = _load()
 
 
 def strerror(status: int) -> str:
-    return lib.ps_strerror(int(status)).decode()
+    text = lib.ps_strerror(int(status)).decode()
+    if status == PS_EHIP:
+        text += ": " + ps_last_hip_error()
+    return text
+
+
+def ps_last_hip_error() -> str:
+    return lib.ps_last_hip_error().decode()
 
 
 def _ptr(t) -> int:

@@ -240,6 +240,8 @@ extern "C" int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, cons
                        (hipStream_t)stream, (const float *)e->bias, epi);
 }
 
+extern "C" const char *ps_last_hip_error(void) { return last_hip_error_text(); }
+
 extern "C" int ps_tile_valid(const ps_conv_desc *d, const ps_tile *t)
 {
     Dims dm;

@@ -25,7 +25,18 @@ int make_dims(const ps_conv_desc *d, Dims *out);
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-inline int hip_status(hipError_t e) { return e == hipSuccess ? PS_OK : PS_EHIP; }
+// Remembers the runtime's own description of the last failure for ps_last_hip_error().
+inline const char *&last_hip_error_text()
+{
+    static thread_local const char *text = "";
+    return text;
+}
+inline int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return PS_OK;
+    last_hip_error_text() = hipGetErrorString(e);
+    return PS_EHIP;
+}
 
 // conv_fwd_*.hip
 int launch_conv_f32(const Dims &dm, const ps_tile &t, const float *in, const float *wt, float *out,
