@@ -104,6 +104,9 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
         if (rc != PS_OK) return rc;
     }
     a.plane_bytes = dm.H * dm.W * kBlock * dm.es;
+    const auto magic = [](int d) { return d == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)d); };
+    a.magic_split = magic(a.c_split);
+    a.magic_inner = magic(a.raster == 0 ? a.n_kt : a.n_mt);
     a.magic_pq = a.PQ == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.PQ);
     a.magic_q = a.Q == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.Q);
     a.out_bytes = (unsigned)((size_t)dm.M * dm.K * 4);

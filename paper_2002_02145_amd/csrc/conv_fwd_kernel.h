@@ -58,6 +58,7 @@ struct ConvArgs {
     int nb_split;  // batch elements per split
     int c_split;
     int n_mt, n_kt;
+    unsigned magic_split, magic_inner;  // floor(2^32 / c_split), floor(2^32 / (raster == 0 ? n_kt : n_mt))
     const float *bias;  // per output channel, added before the store (epi & 1)
     int epi;            // fused epilogue: 1 = add bias, 2 = max(x, 0), 4 = store bf16 (round to nearest even)
     int raster;
@@ -108,15 +109,14 @@ __device__ inline TileCoord decode_tile(const ConvArgs &a)
     const int nwg = a.n_mt * a.n_kt * a.c_split;
     int L = xcd_contiguous_index((int)blockIdx.x, nwg);
     TileCoord tc;
-    tc.split = L % a.c_split;
-    L /= a.c_split;
-    if (a.raster == 0) {
-        tc.ktile = L % a.n_kt;
-        tc.mtile = L / a.n_kt;
-    } else {
-        tc.mtile = L % a.n_mt;
-        tc.ktile = L / a.n_mt;
-    }
+    // divisions by reciprocal multiplication: a generic 32-bit division is ~35 instructions, and everything a
+    // workgroup issues before its first MFMA competes with the MFMA streams of its neighbours on the SIMD
+    tc.split = 0;
+    if (a.c_split > 1) fast_divmod(L, a.c_split, a.magic_split, L, tc.split);
+    if (a.raster == 0)
+        fast_divmod(L, a.n_kt, a.magic_inner, tc.mtile, tc.ktile);
+    else
+        fast_divmod(L, a.n_mt, a.magic_inner, tc.ktile, tc.mtile);
     return tc;
 }
 
