@@ -123,3 +123,25 @@ def test_resnet50_sweep(dtype):
             nn, k, p, q = (int(rng.integers(v)) for v in (shape.N, shape.K, shape.P, shape.Q))
             o, m = oracle.conv2d_fwd_point(shape, x, w, nn, k, p, q)
             assert abs(got[nn, k, p, q] - o) <= TOL[dtype] * m, shape.name
+
+
+@pytest.mark.parametrize("shape", [
+    # blocked input of 2 * 4 * 2040 * 2040 * 64 B = 0.992 * 2^31 bytes: the largest byte offsets the kernels form
+    wl.ConvShape(2, 64, 2040, 2040, 16, 1, 1, 2, 0, "input_near_2GiB"),
+    # output of 4 * 512 * 510 * 510 * 4 B = 0.992 * 2^31 bytes
+    wl.ConvShape(4, 16, 510, 510, 512, 1, 1, 1, 0, "output_near_2GiB"),
+], ids=lambda s: s.name)
+def test_tensors_near_the_size_limit(shape):
+    """32-bit byte offsets up to the documented limit of 2 GiB per tensor: every output element against the oracle;
+    one element more per side is refused."""
+    from gpu_util import run_conv
+    x, w = wl.relu_like(shape, 77)
+    got = run_conv(shape, x, w, 0, ws=True)
+    out, mag = oracle.conv2d_fwd(shape, x, w)
+    assert oracle.normalised_error(got, out, mag) <= TOL[0]
+    del got, out, mag
+    too_big = wl.ConvShape(shape.N, shape.C, shape.H + 32, shape.W + 32, shape.K, 1, 1, shape.stride, 0)
+    from paper_2002_02145_amd import binding as ps
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_out_dims(ps.ConvDesc.of(too_big))
+    assert e.value.status == ps.PS_EUNSUPPORTED
