@@ -1,4 +1,5 @@
 // C ABI entry points: descriptor validation, size queries, convolution launch.
+#include <algorithm>
 #include <mutex>
 
 #include "conv_fwd_kernel.h"
@@ -51,7 +52,7 @@ const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 }
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -59,7 +60,8 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     int n = 0;
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     n = n < cap ? n : cap;
-    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group};
+    for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group,
+                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0};
     return n;
 }
 
@@ -74,6 +76,23 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     const long long n_mt = (dm.M + t.mt - 1) / t.mt;
     if (n_mt * ((dm.K + t.kt - 1) / t.kt) * t.c_split > (1LL << 30)) return PS_EUNSUPPORTED;
     return PS_OK;
+}
+
+// The patch kernels serve 3x3 / stride 1 / pad 1 on c-block-aligned ranges, if the extended rows of every pixel
+// tile (its rows, one more above and below, two zero rows per image boundary inside it) fit the patch.
+bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes)
+{
+    if (dm.dtype != PS_BF16 || dm.R != 3 || dm.S != 3 || dm.stride != 1 || dm.pad != 1) return false;
+    if ((dm.NB / t.c_split) % 9 != 0) return false;
+    const long long PQ = (long long)dm.P * dm.Q;
+    int worst = 0;
+    for (long long m0 = 0; m0 < dm.M; m0 += t.mt) {
+        const long long ml = std::min<long long>(m0 + t.mt, dm.M) - 1;
+        const long long e0 = (m0 / PQ) * (dm.H + 2) + (m0 % PQ) / dm.Q;
+        const long long e1 = (ml / PQ) * (dm.H + 2) + (ml % PQ) / dm.Q + 2;
+        worst = std::max(worst, (int)(e1 - e0 + 1));
+    }
+    return (long long)worst * (dm.W + 2) * 32 <= capacity_bytes;
 }
 
 int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, float *ws, hipStream_t st,
@@ -106,6 +125,8 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     a.plane_bytes = dm.H * dm.W * kBlock * dm.es;
     const auto magic = [](int d) { return d == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)d); };
     a.magic_split = magic(a.c_split);
+    a.magic_pitch = magic(dm.W + 2);
+    a.magic_h2 = magic(dm.H + 2);
     a.magic_inner = magic(a.raster == 0 ? a.n_kt : a.n_mt);
     a.magic_pq = a.PQ == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.PQ);
     a.magic_q = a.Q == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.Q);
@@ -120,6 +141,7 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
         fn = sh->launch_7x7p;
         a.nb_split = 14;  // 7 filter rows x 2 groups of 4 taps; a.NB stays 49 for filter addressing
     }
+    if (sh->launch_halo && halo_applies(dm, t, sh->halo_bytes)) fn = sh->launch_halo;
     fn(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
     rc = hip_status(hipGetLastError());
     if (rc != PS_OK) return rc;

@@ -12,6 +12,7 @@
 //   * A batch element is only 32 matrix-core cycles per 32x32 tile, so an iteration (one barrier) handles
 //     G batch elements and a ring slot holds G elements.
 #include "conv_fwd_kernel.h"
+#include "conv_fwd_bf16_halo.h"
 
 namespace ps {
 
@@ -286,7 +287,8 @@ void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
 #define PS_BF16_SHAPE(KT, MT, WK, WM, NBUF, G)                                                          \
     {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES, G,              \
      &launch_bf16<KT, MT, WK, WM, NBUF, G, 0>, &launch_bf16<KT, MT, WK, WM, NBUF, G, 1>,                 \
-     &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, nullptr}
+     &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, nullptr, halo_launch_or_null<KT, MT, WK, WM, NBUF>(),        \
+     halo_capacity_bytes<MT>()}
 #define PS_BF16_RINGS(KT, MT, WK, WM, G) PS_BF16_SHAPE(KT, MT, WK, WM, 2, G), PS_BF16_SHAPE(KT, MT, WK, WM, 4, G)
 
 //                 KT   MT  WK WM  G        wave tile (channels x pixels)

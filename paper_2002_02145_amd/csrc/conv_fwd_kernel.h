@@ -58,7 +58,8 @@ struct ConvArgs {
     int nb_split;  // batch elements per split
     int c_split;
     int n_mt, n_kt;
-    unsigned magic_split, magic_inner;  // floor(2^32 / c_split), floor(2^32 / (raster == 0 ? n_kt : n_mt))
+    unsigned magic_split, magic_inner;
+    unsigned magic_pitch, magic_h2;     // floor(2^32 / (W + 2)), floor(2^32 / (H + 2)): patch rows of the 3x3 kernels  // floor(2^32 / c_split), floor(2^32 / (raster == 0 ? n_kt : n_mt))
     const float *bias;  // per output channel, added before the store (epi & 1)
     int epi;            // fused epilogue: 1 = add bias, 2 = max(x, 0), 4 = store bf16 (round to nearest even)
     int raster;
@@ -569,6 +570,8 @@ struct ShapeEntry {
     LaunchFn launch_1x1;  // R = S = 1 baked in (nullptr if not compiled)
     LaunchFn launch_3x3;  // R = S = 3 baked in
     LaunchFn launch_7x7p; // R = S = 7, C <= 4: tap-packed
+    LaunchFn launch_halo; // 3x3, stride 1, pad 1 with the input patch staged once per c-block (nullptr if none)
+    int halo_bytes;       // capacity of that kernel's patch
 };
 
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
@@ -580,6 +583,6 @@ void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
     {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES, 1,                   \
      &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
-     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32<KT, MT, WK, WM, NBUF, 7>}
+     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32<KT, MT, WK, WM, NBUF, 7>, nullptr, 0}
 
 }  // namespace ps

@@ -22,9 +22,10 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
+bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes);  // api.hip
 
 namespace {
 
@@ -66,7 +67,7 @@ bool baked_filter(const Dims &dm, int nb_split)
 int group_of(const Dims &dm, const ShapeInfo &sh, int nb_split)
 {
     if (dm.dtype == PS_F32) return 1;
-    return baked_filter(dm, nb_split) && dm.R == 3 ? 3 : sh.group;
+    return baked_filter(dm, nb_split) && dm.R == 3 ? 3 : sh.group;  // (the patch kernel: see model_cost)
 }
 
 // batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples
@@ -107,6 +108,9 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const bool baked = baked_filter(dm, dm.NB / t.c_split);
     const double es = dm.es;
     const double waves_wg = sh.threads / 64.0;
+    // 16-bit 3x3 / stride 1 / pad 1: the ring-2 rows of a shape run the kernel that stages the input patch once per
+    // c-block (two slots of one c-block each) instead of gathering every tap
+    const bool patch = sh.halo_bytes > 0 && halo_applies(dm, t, sh.halo_bytes);
 
     // ---- residency --------------------------------------------------------------------------------
     const double tiles_wave = (double)t.kt * t.mt / (waves_wg * 1024.0);  // 32x32 MFMA tiles per wave
@@ -126,7 +130,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     // per batch element a wave also pays a barrier and the issue of its loads and LDS reads; with a
     // single resident wave per SIMD nothing hides that
     const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
-    const double grp = group_of(dm, sh, dm.NB / t.c_split);  // batch elements per loop iteration
+    const double grp = patch ? 9.0 : group_of(dm, sh, dm.NB / t.c_split);  // batch elements per loop iteration
     const double n_iter = nb_pad / grp;
     double clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * n_iter;
     // a load issued in iteration b must have landed (ring - 1) iterations later: the part of the latency
@@ -145,7 +149,12 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double wt_bytes = (double)dm.Kb * 16.0 * dm.Cb * 16.0 * dm.R * dm.S * es;
     const double out_bytes = M * dm.K * 4.0;
     // into the CUs: every workgroup gathers its pixels and its filter slice once per batch element
-    const double cu_bytes = nwg * nb_pad * 16.0 * es * (t.mt + t.kt);
+    double cu_bytes = nwg * nb_pad * 16.0 * es * (t.mt + t.kt);
+    if (patch) {
+        // rows of the tile plus a row above and below, pitch W + 2, once per c-block; filters as before
+        const double rows = std::ceil((double)t.mt / dm.Q) + 3.0;
+        cu_bytes = nwg * (nb_pad / 9.0) * (rows * (dm.W + 2) * 16.0 * es + 9.0 * 16.0 * es * t.kt);
+    }
     // what one XCD's resident workgroups touch between two uses of the same data
     const double wg_xcd = std::min(nwg, c.cus * occ) / c.xcds;
     double xcd_ws;
