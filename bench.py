@@ -229,7 +229,8 @@ def main(argv=None) -> int:
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4)}
     roof.update({"traffic": traffic, "traffic_unit": "bytes per launch (HBM side)", "algorithmic_bytes": alg_bytes,
-                 "kernel": "conv_fwd_%s_kernel<kt=%d,mt=%d,ring=%d>" % (a.dtype, tile.kt, tile.mt, tile.ring),
+                 "kernel": "conv_fwd_%s %s loop <kt=%d,mt=%d,ring=%d>" % (a.dtype, ps.KERNEL_NAMES[ps.ps_tile_kernel(d, tile)],
+                                                                           tile.kt, tile.mt, tile.ring),
                  "kernel_us": round(kernel_ms * 1e3, 2), "isolated_launch_us": round(each_ms * 1e3, 2),
                  "launches_per_step": 1 if tile.c_split == 1 else 2, "flop_per_launch": shape.flops})
     line = {

@@ -145,6 +145,19 @@ int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us);
 /* Same for ps_conv2d_fwd_ws: only candidates whose workspace fits in `workspace_bytes` compete. */
 int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *best, double *modelled_us);
 
+/* Which inner loop the library runs for tile `t` on `d` (for reports and tests): the loop with a runtime filter size,
+ * the loops with a 1x1 or 3x3 filter baked in, the 7x7 loop that packs four taps of up to four channels into one
+ * batch element, or the 16-bit 3x3 loop that stages the input patch once per c-block.  Negative ps_status if the
+ * tile is not valid for the descriptor. */
+typedef enum {
+    PS_KERNEL_GENERAL = 0,
+    PS_KERNEL_1X1 = 1,
+    PS_KERNEL_3X3 = 3,
+    PS_KERNEL_PACKED_7X7 = 7,
+    PS_KERNEL_PATCH_3X3 = 9
+} ps_kernel_variant;
+int ps_tile_kernel(const ps_conv_desc *d, const ps_tile *t);
+
 const char *ps_strerror(int status);
 /* The HIP runtime's description of the last PS_EHIP this thread received ("" if none); static storage. */
 const char *ps_last_hip_error(void);

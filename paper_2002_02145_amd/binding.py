@@ -105,6 +105,7 @@ def _load() -> ctypes.CDLL:
         "ps_workspace_bytes": (ctypes.c_size_t, [dp, tp]),
         "ps_conv2d_fwd_ws": (ctypes.c_int, [dp, tp, vp, vp, vp, vp, ctypes.c_size_t, vp]),
         "ps_conv2d_fwd_fused": (ctypes.c_int, [dp, tp, ctypes.POINTER(Epilogue), vp, vp, vp, vp, ctypes.c_size_t, vp]),
+        "ps_tile_kernel": (ctypes.c_int, [dp, tp]),
         "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_tile_count": (ctypes.c_int, [dp]),
@@ -221,6 +222,16 @@ def ps_conv2d_fwd_fused(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace
     tp = ctypes.byref(tile) if tile is not None else None
     _check(lib.ps_conv2d_fwd_fused(ctypes.byref(desc), tp, ctypes.byref(e), _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk),
                                    _ptr(workspace) or None, int(workspace_bytes), _stream(stream)), "ps_conv2d_fwd_fused")
+
+
+KERNEL_NAMES = {0: "general", 1: "1x1 baked", 3: "3x3 baked", 7: "7x7 tap-packed", 9: "3x3 patch"}
+
+
+def ps_tile_kernel(desc: ConvDesc, tile: Tile) -> int:
+    v = lib.ps_tile_kernel(ctypes.byref(desc), ctypes.byref(tile))
+    if v < 0:
+        raise PsError(v, "ps_tile_kernel")
+    return v
 
 
 def ps_tile_cost_ws_us(desc: ConvDesc, tile: Tile) -> float:

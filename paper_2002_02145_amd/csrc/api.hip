@@ -95,6 +95,20 @@ bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes)
     return (long long)worst * (dm.W + 2) * 32 <= capacity_bytes;
 }
 
+// Which loop runs a tile: the filter size is baked into the loop when a specialised kernel exists and the
+// (split) range falls on c-block boundaries.
+int kernel_variant(const Dims &dm, const ps_tile &t, const ShapeEntry &sh)
+{
+    const int nb_split = dm.NB / t.c_split;
+    if (sh.launch_halo && halo_applies(dm, t, sh.halo_bytes)) return PS_KERNEL_PATCH_3X3;
+    if (packs_taps(dm) && t.c_split == 1 && sh.launch_7x7p) return PS_KERNEL_PACKED_7X7;
+    if (dm.R == dm.S && nb_split % (dm.R * dm.S) == 0) {
+        if (dm.R == 1 && sh.launch_1x1) return PS_KERNEL_1X1;
+        if (dm.R == 3 && sh.launch_3x3) return PS_KERNEL_3X3;
+    }
+    return PS_KERNEL_GENERAL;
+}
+
 int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, float *ws, hipStream_t st,
                 const float *bias = nullptr, int epi = 0)
 {
@@ -131,17 +145,17 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     a.magic_pq = a.PQ == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.PQ);
     a.magic_q = a.Q == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.Q);
     a.out_bytes = (unsigned)((size_t)dm.M * dm.K * 4);
-    // filter size baked into the loop when a specialised kernel exists and splits fall on c-block boundaries
     LaunchFn fn = sh->launch;
-    if (dm.R == dm.S && a.nb_split % (dm.R * dm.S) == 0) {
-        if (dm.R == 1 && sh->launch_1x1) fn = sh->launch_1x1;
-        if (dm.R == 3 && sh->launch_3x3) fn = sh->launch_3x3;
-    }
-    if (packs_taps(dm) && t.c_split == 1 && sh->launch_7x7p) {
+    switch (kernel_variant(dm, t, *sh)) {
+    case PS_KERNEL_1X1: fn = sh->launch_1x1; break;
+    case PS_KERNEL_3X3: fn = sh->launch_3x3; break;
+    case PS_KERNEL_PATCH_3X3: fn = sh->launch_halo; break;
+    case PS_KERNEL_PACKED_7X7:
         fn = sh->launch_7x7p;
         a.nb_split = 14;  // 7 filter rows x 2 groups of 4 taps; a.NB stays 49 for filter addressing
+        break;
+    default: break;
     }
-    if (sh->launch_halo && halo_applies(dm, t, sh->halo_bytes)) fn = sh->launch_halo;
     fn(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
     rc = hip_status(hipGetLastError());
     if (rc != PS_OK) return rc;
@@ -263,6 +277,17 @@ extern "C" int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, cons
     const int epi = (e->bias ? 1 : 0) | (e->relu ? 2 : 0) | (e->out_dtype == PS_BF16 ? 4 : 0);
     return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr,
                        (hipStream_t)stream, (const float *)e->bias, epi);
+}
+
+extern "C" int ps_tile_kernel(const ps_conv_desc *d, const ps_tile *t)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!t) return PS_EINVAL;
+    rc = tile_valid(dm, *t);
+    if (rc != PS_OK) return rc;
+    return kernel_variant(dm, *t, *find_shape(dm.dtype, t->kt, t->mt, t->ring));
 }
 
 extern "C" const char *ps_last_hip_error(void) { return last_hip_error_text(); }
