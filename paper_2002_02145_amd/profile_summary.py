@@ -22,7 +22,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 def kernel_source_digest(dtype: str = "f32") -> str:
     """Digest of the sources that decide what the convolution kernel of `dtype` ("f32" or "bf16") does."""
     h = hashlib.sha256()
-    for f in ("conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip", "api.hip"):
+    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip", "api.hip"] + (["conv_fwd_bf16_halo.h"] if dtype == "bf16" else [])
+    for f in files:
         with open(os.path.join(HERE, "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
