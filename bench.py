@@ -65,10 +65,10 @@ def _time_each(fn, launches: int):
 
 # HBM-side bytes per launch of the headline kernel from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each
 # scaled by a reference copy; see profiles/), keyed by a digest of the kernel sources they were taken with.
-# A different digest, or a different tile picked by the model, means the launch is not the one the counters were
+# A different digest, a different tile picked by the model or a different inner loop means the launch is not the one the counters were
 # taken on: traffic is then reported as null.
-MEASURED_TRAFFIC = {"f32": ("b1a525ef42cd280f", (64, 128, 4, 1, 0), 46656137),
-                    "bf16": ("da4521ba0aa9c439", (64, 256, 2, 1, 0), 34614104)}
+MEASURED_TRAFFIC = {"f32": ("2da7b7b17ab071f5", (64, 128, 4, 1, 0), 3, 46656137),
+                    "bf16": ("4bffab3e3c4e769c", (64, 256, 2, 1, 0), 9, 34614104)}
 
 
 def main(argv=None) -> int:
@@ -143,8 +143,9 @@ def main(argv=None) -> int:
     # adds the plane-adding pass to every step, and its time is charged to the convolution kernel as well
     kernel_ms = ev_ms
     from paper_2002_02145_amd.profile_summary import kernel_source_digest
-    digest, ttile, tbytes = MEASURED_TRAFFIC.get(a.dtype, (None, None, None))
-    same_launch = digest == kernel_source_digest(a.dtype) and ttile == (tile.kt, tile.mt, tile.ring, tile.c_split, tile.raster)
+    digest, ttile, tvariant, tbytes = MEASURED_TRAFFIC.get(a.dtype, (None, None, None, None))
+    same_launch = (digest == kernel_source_digest(a.dtype) and ttile == tile.as_tuple()
+                   and tvariant == ps.ps_tile_kernel(d, tile))
     traffic = tbytes if same_launch else None
 
     # transforms: bytes moved (read + write) per call

@@ -1,6 +1,5 @@
 // C ABI entry points: descriptor validation, size queries, convolution launch.
 #include <algorithm>
-#include <mutex>
 
 #include "conv_fwd_kernel.h"
 

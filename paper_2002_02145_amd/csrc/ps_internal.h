@@ -38,14 +38,7 @@ inline int hip_status(hipError_t e)
     return PS_EHIP;
 }
 
-// conv_fwd_*.hip
-int launch_conv_f32(const Dims &dm, const ps_tile &t, const float *in, const float *wt, float *out,
-                    hipStream_t stream);
-int launch_conv_bf16(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out,
-                     hipStream_t stream);
-bool conv_shape_compiled(int dtype, int kt, int mt, int ring);
-int conv_shape_lds_bytes(int dtype, int kt, int mt, int ring);
-int conv_shape_threads(int dtype, int kt, int mt, int ring);
+// api.hip / conv_fwd_f32.hip
 bool packs_taps(const Dims &dm);
 int launch_fill_zero(float *p, size_t n, hipStream_t stream);
 int launch_reduce_planes(const float *partial, void *out, size_t n, int planes, const float *bias, int epi, int PQ, int Kb,

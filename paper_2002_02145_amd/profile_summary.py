@@ -20,9 +20,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 def kernel_source_digest(dtype: str = "f32") -> str:
-    """Digest of the sources that decide what the convolution kernel of `dtype` ("f32" or "bf16") does."""
+    """Digest of the kernel sources of `dtype` ("f32" or "bf16"); which tile and which inner loop run is recorded
+    beside it."""
     h = hashlib.sha256()
-    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip", "api.hip"] + (["conv_fwd_bf16_halo.h"] if dtype == "bf16" else [])
+    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip"] + (["conv_fwd_bf16_halo.h"] if dtype == "bf16" else [])
     for f in files:
         with open(os.path.join(HERE, "csrc", f), "rb") as fh:
             h.update(fh.read())
