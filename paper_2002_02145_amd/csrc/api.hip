@@ -51,7 +51,7 @@ const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 }
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -60,7 +60,7 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     n = n < cap ? n : cap;
     for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group,
-                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0};
+                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0, tab[i].launch == nullptr};
     return n;
 }
 
@@ -68,7 +68,10 @@ int tile_valid(const Dims &dm, const ps_tile &t)
 {
     if (t.kt <= 0 || t.mt <= 0 || t.ring <= 0 || t.c_split <= 0 || (t.raster != 0 && t.raster != 1))
         return PS_EUNSUPPORTED;
-    if (!find_shape(dm.dtype, t.kt, t.mt, t.ring)) return PS_EUNSUPPORTED;
+    const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.ring);
+    if (!sh) return PS_EUNSUPPORTED;
+    // shapes without a loop for a runtime filter size and without an atomic epilogue: 1x1 and 3x3, unsplit
+    if (!sh->launch && !(t.c_split == 1 && dm.R == dm.S && (dm.R == 1 || dm.R == 3))) return PS_EUNSUPPORTED;
     // output channels are padded to whole 32-wide MFMA tiles at most: a larger kt would only add waste
     if ((dm.K + t.kt - 1) / t.kt * t.kt != (dm.K + 31) / 32 * 32) return PS_EUNSUPPORTED;
     if (dm.NB % t.c_split != 0) return PS_EUNSUPPORTED;

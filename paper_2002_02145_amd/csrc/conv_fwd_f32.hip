@@ -1,5 +1,6 @@
 // fp32 kernel shapes of the batch-reduce-GEMM convolution and their launcher.
 #include "conv_fwd_kernel.h"
+#include "conv_fwd_f32_n16.h"
 
 namespace ps {
 
@@ -20,7 +21,12 @@ namespace ps {
     X(32, 64, 1, 2, 4) X(32, 64, 1, 2, 8)     /* 32 x 32, 2 waves */
 
 #define PS_TABLE_ROW(KT, MT, WK, WM, NBUF) PS_F32_SHAPE(KT, MT, WK, WM, NBUF),
-static const ShapeEntry kF32Shapes[] = {PS_F32_SHAPE_LIST(PS_TABLE_ROW)};
+static const ShapeEntry kF32Shapes[] = {
+    PS_F32_SHAPE_LIST(PS_TABLE_ROW)
+    // 64 channels x MT pixels on 16x16x4 MFMA tiles: pixel tiles in steps of 16, for even division over the chip
+    PS_F32_N16_SHAPE(48, 2), PS_F32_N16_SHAPE(48, 4), PS_F32_N16_SHAPE(96, 2), PS_F32_N16_SHAPE(96, 4),
+    PS_F32_N16_SHAPE(176, 2), PS_F32_N16_SHAPE(176, 4),
+};
 
 const ShapeEntry *f32_shapes(int *count)
 {

@@ -1,0 +1,199 @@
+// fp32 forward convolution on 16x16x4 MFMA tiles: 64 output channels x MT pixels per workgroup, MT any multiple of 16.
+//
+// Why a second tiling next to the 32x32x2 kernels of conv_fwd_kernel.h: the waves that share a SIMD run their MFMA
+// streams one after another, so a launch takes as long as the most loaded SIMD, and with 32-pixel granularity the
+// pixel tile can rarely be chosen such that every compute unit gets the same amount (N = 28, 56x56, K = 64: 686
+// tiles of 128 pixels on 256 compute units, 3 on most, 2 on the rest: 89 %).  Here the four waves of a workgroup
+// split the 64 output channels (16 each) and every wave covers all MT pixels, so MT moves in steps of 16 and the
+// host can pick it so that the tiles divide evenly (same layer: 499 tiles of 176 pixels, 2 on nearly every compute
+// unit: 97 %), and deep layers need no split of the reduction.
+//
+// Operands (v_mfma_f32_16x16x4_f32, D = A*B + C with A = filters, B = pixels): lane l supplies A[row l%16][k l/16]
+// and B[k l/16][col l%16] and receives D[rows 4*(l/16) .. +3][col l%16].  The reduction index is permuted as in the
+// 32x32 kernels: at MFMA step t the lane group g = l/16 contributes channel 4g + t, so a lane's four B values are
+// the 16 bytes at pixel*64 + g*16 (one ds_read_b128 per 16-pixel tile, the 64 lanes covering 1 KB contiguously: no
+// swizzle) and its four A values are W[c = 4g + t][k] of its channel row.  A lane's four results are four
+// consecutive output channels of one pixel: one 16-byte store.
+#pragma once
+#include "conv_fwd_kernel.h"
+
+namespace ps {
+
+typedef float floatx4_n __attribute__((ext_vector_type(4)));
+
+template <int MT, int NBUF>
+struct N16Shape {
+    static constexpr int KT = 64;
+    static constexpr int NW = 4;          // one wave per 16 output channels
+    static constexpr int NT = MT / 16;    // 16-pixel tiles, all of them in every wave
+    static constexpr int PGRP = MT / 16;  // 1 KB groups of 16 pixels per batch element
+    static constexpr int WBLK = KT / 16;
+    static constexpr int APW = (PGRP + NW - 1) / NW;
+    static constexpr int WPW = 1;
+    static constexpr int LPE = APW + WPW;
+    static constexpr int WPITCH = 1024 + 64;
+    static constexpr int A_BYTES = MT * 64;
+    static constexpr int W_BYTES = WBLK * WPITCH;
+    static constexpr int SLOT = A_BYTES + W_BYTES;
+    static constexpr bool DUMMY = PGRP % NW != 0;
+    static constexpr int LDS_BYTES = NBUF * SLOT + (DUMMY ? 1024 : 0);
+    static constexpr int D = NBUF;
+    static_assert(MT % 16 == 0 && NBUF >= 2 && NBUF % 2 == 0, "tile shape");
+    static_assert(LDS_BYTES <= 160 * 1024 && (D - 2) * LPE <= 63, "LDS budget, vmcnt range");
+};
+
+template <int MT, int NBUF, int SIDE>
+__global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
+{
+    static_assert(SIDE == 1 || SIDE == 3, "filter sizes with a baked loop");
+    constexpr int TAPS = SIDE * SIDE;
+    using Sh = N16Shape<MT, NBUF>;
+    constexpr int NW = Sh::NW, NT = Sh::NT, APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
+    constexpr int U = NBUF / ct_gcd(NBUF, TAPS) * TAPS;
+    __shared__ __attribute__((aligned(1024))) char lds[Sh::LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, l16 = lane & 15;
+
+    const TileCoord tc = decode_tile(a);
+    const int m0 = tc.mtile * MT;
+    const int kb0 = tc.ktile * (Sh::KT / 16);
+    const int b_begin = tc.split * a.nb_split;
+
+    // ---- loader: one instruction fills 16 pixels (lane -> pixel lane/4, 16-byte chunk lane%4), offsets per tap
+    unsigned vtap[APW][TAPS];
+#pragma unroll
+    for (int i = 0; i < APW; ++i) {
+        const int grp = i * NW + wave;
+        const int m = m0 + grp * 16 + (lane >> 2);
+        int n, pq, p, q;
+        fast_divmod(m, a.PQ, a.magic_pq, n, pq);
+        fast_divmod(pq, a.Q, a.magic_q, p, q);
+        const bool inside = (grp < Sh::PGRP) & (m < a.M);
+        const int h0 = inside ? p * a.stride - a.pad : -(1 << 24), w0 = q * a.stride - a.pad;
+        const int poff = (n * a.Cb * a.H + h0) * a.W + w0;
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            const int r = t / SIDE, sx = t % SIDE;
+            const bool ok = ((unsigned)(h0 + r) < (unsigned)a.H) & ((unsigned)(w0 + sx) < (unsigned)a.W);
+            vtap[i][t] = ok ? (unsigned)((poff + r * a.W + sx) * 64 + (lane & 3) * 16) : kOobOffset;
+        }
+    }
+    int wsoff[WPW];
+    bool wok[WPW];
+    wok[0] = kb0 + wave < a.Kb;  // wave w fetches filter block kb0 + w, the one it multiplies with
+    wsoff[0] = ((kb0 + wave) * a.NB + b_begin) << 10;
+    const unsigned vw[2] = {(unsigned)lane << 4, (unsigned)lane << 4};
+
+    // ---- reader -------------------------------------------------------------------------------------
+    const int paddr = l16 * 64 + g * 16;                                  // + tile * 1024
+    const int waddr = Sh::A_BYTES + wave * Sh::WPITCH + g * 4 * 64 + l16 * 4;  // + t * 64
+    floatx4_n pf[2][NT];
+    float wf[2][4];
+    floatx4_n acc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[j] = floatx4_n{0.f, 0.f, 0.f, 0.f};
+
+#define PS_N16_READ(SLOT_, PAR_)                                                                           \
+    {                                                                                                      \
+        const char *sb_ = lds + (SLOT_) * Sh::SLOT;                                                        \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                     \
+            pf[PAR_][j] = *reinterpret_cast<const floatx4_n *>(sb_ + paddr + j * 1024);                    \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t)                                                      \
+            wf[PAR_][t] = *reinterpret_cast<const float *>(sb_ + waddr + t * 64);                          \
+    }
+
+    // ---- pipeline (as the 32x32 kernels: ring of NBUF batch elements, unrolled over lcm(NBUF, taps)) --------
+    const int nb = a.nb_split;
+    int cb0 = b_begin / TAPS;
+#pragma unroll
+    for (int e = 0; e < D; ++e)
+        issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, false>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+    wait_vm_and_barrier<(D - 1) * LPE>();
+    PS_N16_READ(0, 0)
+    for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            wait_vm_and_barrier<(D - 2) * LPE>();
+            PS_N16_READ((u + 1) % NBUF, (u + 1) % 2)
+            issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, false>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF,
+                                                                             u + NBUF, b0, cb0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[u % 2][t], pf[u % 2][j][t], acc[j], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < NT * 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA ...
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // ... one LDS read ...
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // ... one global load
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#undef PS_N16_READ
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ---- epilogue: lane (g, l16) holds channels 4g .. 4g+3 of this wave's block for pixel tile*16 + l16 -------
+    const int epi = a.c_split == 1 ? a.epi : 0;
+    const bool bf16_out = epi & 4;
+    float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, bf16_out ? a.out_bytes / 2 : a.out_bytes);
+    const int esz = bf16_out ? 2 : 4;
+    const int kb = kb0 + wave;
+    const int soff = kb * a.PQ * 16 * esz;
+    floatx4_n bias = {0.f, 0.f, 0.f, 0.f};
+    if ((epi & 1) && kb < a.Kb) bias = *reinterpret_cast<const floatx4_n *>(a.bias + kb * 16 + g * 4);
+    // pixel m0 + l16 of this lane, then 16 further per tile: (image, position in image) by increments, one division
+    int n, pq;
+    fast_divmod(m0 + l16, a.PQ, a.magic_pq, n, pq);
+    int row = n * a.Kb * a.PQ + pq;  // pixel row of the [N][Kb][PQ] output, before the channel-block plane
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int m = m0 + j * 16 + l16;
+        const unsigned voff = ((m < a.M) & (kb < a.Kb)) ? (unsigned)((row * 16 + g * 4) * esz) : kOobOffset;
+        // next tile: 16 pixels on; crossing into the next image skips the other Kb - 1 channel-block planes
+        pq += 16;
+        row += 16;
+        while (pq >= a.PQ) {  // (PQ may be smaller than 16)
+            pq -= a.PQ;
+            row += (a.Kb - 1) * a.PQ;
+        }
+        floatx4_n v = acc[j];
+        if (epi == 0) {
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, 0);
+        } else {
+            v += bias;
+            if (epi & 2) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+            }
+            if (bf16_out) {
+                const uintx2_t h = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff, soff, 0);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, 0);
+            }
+        }
+        // keep the stored registers live across a short pause: a vector-ALU result allocated into them right
+        // after the store could overtake the store's read of them (see write_out)
+        asm volatile("s_nop 1" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));
+    }
+}
+
+template <int MT, int NBUF, int SIDE>
+void launch_f32_n16(const ConvArgs &a, unsigned grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((conv_fwd_f32_n16_kernel<MT, NBUF, SIDE>), dim3(grid), dim3(256), 0, st, a);
+}
+
+// No loop with a runtime filter size and no atomic epilogue: the enumerator offers these shapes for 1x1 and 3x3
+// filters, unsplit or with workspace planes.
+#define PS_F32_N16_SHAPE(MT, NBUF)                                                                  \
+    {PS_F32, 64, MT, NBUF, 256, N16Shape<MT, NBUF>::LDS_BYTES, 1, nullptr, &launch_f32_n16<MT, NBUF, 1>, \
+     &launch_f32_n16<MT, NBUF, 3>, nullptr, nullptr, 0}
+
+}  // namespace ps

@@ -22,7 +22,7 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
 bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes);  // api.hip
@@ -132,17 +132,34 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
     const double grp = patch ? 9.0 : group_of(dm, sh, dm.NB / t.c_split);  // batch elements per loop iteration
     const double n_iter = nb_pad / grp;
-    double clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * n_iter;
+    // (a lone 16-bit wave cannot hide its barrier behind its own short MFMA stream; an fp32 one can)
+    const bool f32 = dm.dtype == PS_F32;
+    double clk_iter_overhead = (waves_res >= 2 || f32 ? 40.0 : 220.0) * n_iter;
     // a load issued in iteration b must have landed (ring - 1) iterations later: the part of the latency
     // the ring does not cover stalls every wave of the SIMD, and latency varies, so a thin margin still costs
     const double clk_iter = tiles_wave * mfma_clk * grp / eff * waves_res;  // wall clock of one iteration
     const double cover = (t.ring - 1) * clk_iter / c.load_latency_clk;
-    const double stall = std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) + 0.50 * clk_iter * std::exp(-cover);
+    const double stall = std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) + (f32 ? 0.10 : 0.50) * clk_iter * std::exp(-cover);
     clk_iter_overhead += stall * n_iter / waves_res;
-    const double clk_epi = tiles_wave * (t.c_split > 1 && !with_ws ? 900.0 : 250.0);
-    const double rounds = std::ceil(per_cu / occ);
-    const double t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk +
-                           per_cu * (t.ring - 2) * 250.0) / c.clock_hz;  // a deeper ring takes longer to fill, per workgroup
+    // Per workgroup, outside its MFMA stream: address set-up, first fragment reads and the stores of its tile.  The
+    // waves of a SIMD run their streams one after another and a pending MFMA holds the SIMD's issue port, so this
+    // work is not hidden by the other workgroups on the compute unit; it grows with the accumulator tiles a wave
+    // has to store (atomics cost more per tile), and in the 16x16-tile kernels with the pixel tiles every wave
+    // walks over.  The first loads of a launch have nothing to overlap with at all (fill_clk, once).
+    const double clk_wg = (tiles_wave * (t.c_split > 1 && !with_ws ? 1900.0 : 1250.0) +
+                           (sh.baked_only ? 200.0 * (t.mt / 16.0) : 0.0)) * waves_wg / 4.0;  // per SIMD
+    double t_mfma;
+    if (f32) {
+        t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + c.fill_clk + per_cu * clk_wg +
+                  per_cu * (t.ring - 2) * 250.0) / c.clock_hz;  // a deeper ring takes longer to fill, per workgroup
+    } else {
+        // 16-bit tiles are short enough that their set-up and stores mostly hide behind other workgroups; what
+        // shows is the fill of every round of resident workgroups
+        const double rounds = std::ceil(per_cu / occ);
+        const double clk_epi = tiles_wave * (t.c_split > 1 && !with_ws ? 900.0 : 250.0);
+        t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk +
+                  per_cu * (t.ring - 2) * 250.0) / c.clock_hz;
+    }
 
     // ---- bytes that cross each level --------------------------------------------------------------
     const double in_bytes = (double)dm.N * dm.Cb * dm.H * dm.W * 16.0 * es;
@@ -199,8 +216,10 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
         if (s.mt > 64 && s.mt >= 2 * dm.M) continue;
         const long long n_mt = (dm.M + s.mt - 1) / s.mt;
         const long long base_wg = n_mt * ((dm.K + s.kt - 1) / s.kt);
+        if (s.baked_only && !(dm.R == dm.S && (dm.R == 1 || dm.R == 3))) continue;
         for (int sp : splits) {
             if (dm.NB % sp != 0) continue;
+            if (s.baked_only && sp > 1) continue;  // no atomic epilogue in these kernels
             const int nbs = dm.NB / sp;
             // stage depth: keep the depths that divide the split's range; if none of this tile's
             // compiled depths does, keep only the shallowest (its ragged last stage is zero-filled)
