@@ -12,7 +12,8 @@
 // and B[k l/16][col l%16] and receives D[rows 4*(l/16) .. +3][col l%16].  The reduction index is permuted as in the
 // 32x32 kernels: at MFMA step t the lane group g = l/16 contributes channel 4g + t, so a lane's four B values are
 // the 16 bytes at pixel*64 + g*16 (one ds_read_b128 per 16-pixel tile, the 64 lanes covering 1 KB contiguously: no
-// swizzle) and its four A values are W[c = 4g + t][k] of its channel row.  A lane's four results are four
+// swizzle) and its four A values are W[c = 4g + t][k] of its channel row (the filter block is re-ordered to [t][g][k] on its
+// way into LDS so that these reads are free of bank conflicts).  A lane's four results are four
 // consecutive output channels of one pixel: one 16-byte store.
 #pragma once
 #include "conv_fwd_kernel.h"
@@ -85,11 +86,15 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     bool wok[WPW];
     wok[0] = kb0 + wave < a.Kb;  // wave w fetches filter block kb0 + w, the one it multiplies with
     wsoff[0] = ((kb0 + wave) * a.NB + b_begin) << 10;
-    const unsigned vw[2] = {(unsigned)lane << 4, (unsigned)lane << 4};
+    // The filter block lands in LDS as [t][g][k]: 16-byte position `lane` takes channel 4g + t, channels-out
+    // 4q .. 4q+3 with t = lane/16, g = (lane/4)%4, q = lane%4, so that at MFMA step t the four lane groups read four
+    // adjacent 64-byte rows (all banks) instead of rows 256 bytes apart (one bank group, four-way conflict).
+    const unsigned wsrc = (unsigned)((4 * ((lane >> 2) & 3) + (lane >> 4)) * 64 + (lane & 3) * 16);
+    const unsigned vw[2] = {wsrc, wsrc};
 
     // ---- reader -------------------------------------------------------------------------------------
     const int paddr = l16 * 64 + g * 16;                                  // + tile * 1024
-    const int waddr = Sh::A_BYTES + wave * Sh::WPITCH + g * 4 * 64 + l16 * 4;  // + t * 64
+    const int waddr = Sh::A_BYTES + wave * Sh::WPITCH + g * 64 + l16 * 4;  // + t * 256
     floatx4_n pf[2][NT];
     float wf[2][4];
     floatx4_n acc[NT];
@@ -102,7 +107,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
         _Pragma("unroll") for (int j = 0; j < NT; ++j)                                                     \
             pf[PAR_][j] = *reinterpret_cast<const floatx4_n *>(sb_ + paddr + j * 1024);                    \
         _Pragma("unroll") for (int t = 0; t < 4; ++t)                                                      \
-            wf[PAR_][t] = *reinterpret_cast<const float *>(sb_ + waddr + t * 64);                          \
+            wf[PAR_][t] = *reinterpret_cast<const float *>(sb_ + waddr + t * 256);                          \
     }
 
     // ---- pipeline (as the 32x32 kernels: ring of NBUF batch elements, unrolled over lcm(NBUF, taps)) --------
