@@ -22,7 +22,8 @@ namespace ps {
 
 typedef float floatx4_n __attribute__((ext_vector_type(4)));
 
-template <int MT, int NBUF>
+// (FUSED only tells the two kernels of a shape apart where a helper is instantiated per shape type)
+template <int MT, int NBUF, bool FUSED = false>
 struct N16Shape {
     static constexpr int KT = 64;
     static constexpr int NW = 4;          // one wave per 16 output channels
@@ -43,12 +44,15 @@ struct N16Shape {
     static_assert(LDS_BYTES <= 160 * 1024 && (D - 2) * LPE <= 63, "LDS budget, vmcnt range");
 };
 
-template <int MT, int NBUF, int SIDE>
+// FUSED = false stores the accumulators as they are (output or a split's partial plane); FUSED = true is the kernel
+// for an unsplit range with a bias / max(., 0) / bf16 epilogue.  Two kernels rather than a branch: the plain one
+// then stores straight from the accumulator registers.
+template <int MT, int NBUF, int SIDE, bool FUSED>
 __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
 {
     static_assert(SIDE == 1 || SIDE == 3, "filter sizes with a baked loop");
     constexpr int TAPS = SIDE * SIDE;
-    using Sh = N16Shape<MT, NBUF>;
+    using Sh = N16Shape<MT, NBUF, FUSED>;
     constexpr int NW = Sh::NW, NT = Sh::NT, APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
     constexpr int U = NBUF / ct_gcd(NBUF, TAPS) * TAPS;
     __shared__ __attribute__((aligned(1024))) char lds[Sh::LDS_BYTES];
@@ -143,56 +147,107 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue: lane (g, l16) holds channels 4g .. 4g+3 of this wave's block for pixel tile*16 + l16 -------
-    const int epi = a.c_split == 1 ? a.epi : 0;
+    // Kept short on purpose: while another wave of the SIMD streams MFMAs these instructions issue slowly, so
+    // their number, not their latency, is what a short-reduction layer pays for.
+    const int kb = kb0 + wave;
+    if (kb >= a.Kb) return;  // (no barrier follows)
+    const int epi = FUSED ? a.epi : 0;
     const bool bf16_out = epi & 4;
     float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
     const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, bf16_out ? a.out_bytes / 2 : a.out_bytes);
     const int esz = bf16_out ? 2 : 4;
-    const int kb = kb0 + wave;
-    const int soff = kb * a.PQ * 16 * esz;
     floatx4_n bias = {0.f, 0.f, 0.f, 0.f};
-    if ((epi & 1) && kb < a.Kb) bias = *reinterpret_cast<const floatx4_n *>(a.bias + kb * 16 + g * 4);
-    // pixel m0 + l16 of this lane, then 16 further per tile: (image, position in image) by increments, one division
-    int n, pq;
-    fast_divmod(m0 + l16, a.PQ, a.magic_pq, n, pq);
-    int row = n * a.Kb * a.PQ + pq;  // pixel row of the [N][Kb][PQ] output, before the channel-block plane
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int m = m0 + j * 16 + l16;
-        const unsigned voff = ((m < a.M) & (kb < a.Kb)) ? (unsigned)((row * 16 + g * 4) * esz) : kOobOffset;
-        // next tile: 16 pixels on; crossing into the next image skips the other Kb - 1 channel-block planes
-        pq += 16;
-        row += 16;
-        while (pq >= a.PQ) {  // (PQ may be smaller than 16)
-            pq -= a.PQ;
-            row += (a.Kb - 1) * a.PQ;
-        }
-        floatx4_n v = acc[j];
-        if (epi == 0) {
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, 0);
-        } else {
-            v += bias;
-            if (epi & 2) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
-            }
-            if (bf16_out) {
-                const uintx2_t h = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff, soff, 0);
-            } else {
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, 0);
-            }
-        }
-        // keep the stored registers live across a short pause: a vector-ALU result allocated into them right
-        // after the store could overtake the store's read of them (see write_out)
-        asm volatile("s_nop 1" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));
+    if (epi & 1) bias = *reinterpret_cast<const floatx4_n *>(a.bias + kb * 16 + g * 4);
+
+// what the fused epilogue does to one accumulator quad before it is stored
+#define PS_N16_FUSED_STORE(V_, VOFF_, SOFF_)                                                               \
+    {                                                                                                      \
+        floatx4_n v_ = (V_) + bias;                                                                        \
+        if (epi & 2) {                                                                                     \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) v_[i_] = fmaxf(v_[i_], 0.f);                  \
+        }                                                                                                  \
+        if (bf16_out) {                                                                                    \
+            const uintx2_t h_ = {pack_bf16(v_[0], v_[1]), pack_bf16(v_[2], v_[3])};                        \
+            __builtin_amdgcn_raw_buffer_store_b64(h_, rout, VOFF_, SOFF_, 0);                              \
+        } else {                                                                                           \
+            const uintx4_t u_ = __builtin_bit_cast(uintx4_t, v_);                                          \
+            __builtin_amdgcn_raw_buffer_store_b128(u_, rout, VOFF_, SOFF_, 0);                             \
+            /* keep the four stored registers live across a short pause: a vector-ALU result allocated */  \
+            /* into them right after the store could overtake the store's read of them (see write_out) */  \
+            asm volatile("s_nop 1" ::"v"(u_));                                                             \
+        }                                                                                                  \
     }
+
+    if (a.PQ >= 16) {
+        // The 16 pixels of a quad start at the wave-uniform pixel m0 + 16 j = (image n_j, position r_j): everything
+        // that depends on j stays in scalar registers (running r_j and the byte offset S_j of (n_j, kb, r_j), which
+        // goes into the store's scalar offset), and a lane only has to notice whether its pixel r_j + l16 has run
+        // over into the next image, which lies Kb - 1 channel-block planes further on.
+        int n0, r;
+        fast_divmod(m0, a.PQ, a.magic_pq, n0, r);
+        n0 = __builtin_amdgcn_readfirstlane(n0);
+        r = __builtin_amdgcn_readfirstlane(r);
+        const int plane = a.PQ * 16 * esz;
+        const int delta = (a.Kb - 1) * plane;
+        int S = (n0 * a.Kb + kb) * plane + r * 16 * esz;
+        const unsigned vlane = (unsigned)((l16 * 16 + g * 4) * esz);
+        const unsigned vnext = vlane + (unsigned)delta;
+        const bool full = m0 + MT <= a.M;
+#define PS_N16_STORE_LOOP(PLAIN_, FULL_)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                       \
+        unsigned voff = l16 >= a.PQ - r ? vnext : vlane;                                                   \
+        if (!(FULL_)) voff = l16 < a.M - m0 - j * 16 ? voff : kOobOffset;                                  \
+        if constexpr (PLAIN_) {                                                                            \
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff, S, 0); \
+        } else {                                                                                           \
+            PS_N16_FUSED_STORE(acc[j], voff, S)                                                            \
+        }                                                                                                  \
+        r += 16;                                                                                           \
+        S += 256 * esz;                                                                                    \
+        if (r >= a.PQ) {                                                                                   \
+            r -= a.PQ;                                                                                     \
+            S += delta;                                                                                    \
+        }                                                                                                  \
+    }
+        if (full) {
+            PS_N16_STORE_LOOP(!FUSED, true)
+        } else {
+            PS_N16_STORE_LOOP(!FUSED, false)
+        }
+#undef PS_N16_STORE_LOOP
+    } else {
+        // images of fewer than 16 pixels: a quad can span several, every lane tracks its own (image, position)
+        const int soff = kb * a.PQ * 16 * esz;
+        int n, pq;
+        fast_divmod(m0 + l16, a.PQ, a.magic_pq, n, pq);
+        int row = n * a.Kb * a.PQ + pq;  // pixel row of the [N][Kb][PQ] output, before the channel-block plane
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int m = m0 + j * 16 + l16;
+            const unsigned voff = m < a.M ? (unsigned)((row * 16 + g * 4) * esz) : kOobOffset;
+            pq += 16;
+            row += 16;
+            while (pq >= a.PQ) {
+                pq -= a.PQ;
+                row += (a.Kb - 1) * a.PQ;
+            }
+            if constexpr (FUSED) {
+                PS_N16_FUSED_STORE(acc[j], voff, soff)
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff, soff, 0);
+            }
+        }
+    }
+#undef PS_N16_FUSED_STORE
 }
 
 template <int MT, int NBUF, int SIDE>
 void launch_f32_n16(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((conv_fwd_f32_n16_kernel<MT, NBUF, SIDE>), dim3(grid), dim3(256), 0, st, a);
+    if (a.epi != 0 && a.c_split == 1)
+        hipLaunchKernelGGL((conv_fwd_f32_n16_kernel<MT, NBUF, SIDE, true>), dim3(grid), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((conv_fwd_f32_n16_kernel<MT, NBUF, SIDE, false>), dim3(grid), dim3(256), 0, st, a);
 }
 
 // No loop with a runtime filter size and no atomic epilogue: the enumerator offers these shapes for 1x1 and 3x3
