@@ -147,11 +147,13 @@ int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *be
 
 /* Which inner loop the library runs for tile `t` on `d` (for reports and tests): the loop with a runtime filter size,
  * the loops with a 1x1 or 3x3 filter baked in, the 7x7 loop that packs four taps of up to four channels into one
- * batch element, or the 16-bit 3x3 loop that stages the input patch once per c-block.  Negative ps_status if the
- * tile is not valid for the descriptor. */
+ * batch element, the 16-bit 3x3 loop that stages the input patch once per c-block, or the fp32 1x1 loop that keeps a
+ * tile's pixels with all 64 input channels in LDS and walks over four 64-channel output tiles (tile kt = 256).
+ * Negative ps_status if the tile is not valid for the descriptor. */
 typedef enum {
     PS_KERNEL_GENERAL = 0,
     PS_KERNEL_1X1 = 1,
+    PS_KERNEL_STATIONARY_1X1 = 2,
     PS_KERNEL_3X3 = 3,
     PS_KERNEL_PACKED_7X7 = 7,
     PS_KERNEL_PATCH_3X3 = 9

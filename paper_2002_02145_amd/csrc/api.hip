@@ -51,7 +51,7 @@ const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 }
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -60,7 +60,7 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     n = n < cap ? n : cap;
     for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group,
-                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0, tab[i].launch == nullptr};
+                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0, tab[i].launch == nullptr, tab[i].stationary};
     return n;
 }
 
@@ -72,6 +72,9 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     if (!sh) return PS_EUNSUPPORTED;
     // shapes without a loop for a runtime filter size and without an atomic epilogue: 1x1 and 3x3, unsplit
     if (!sh->launch && !(t.c_split == 1 && dm.R == dm.S && (dm.R == 1 || dm.R == 3))) return PS_EUNSUPPORTED;
+    // pixel-stationary shapes: 1x1 filters over exactly 4 c-blocks, images of at least 16 pixels
+    if (sh->stationary && !(dm.R == 1 && dm.S == 1 && t.c_split == 1 && dm.Cb == 4 && dm.P * dm.Q >= 16))
+        return PS_EUNSUPPORTED;
     // output channels are padded to whole 32-wide MFMA tiles at most: a larger kt would only add waste
     if ((dm.K + t.kt - 1) / t.kt * t.kt != (dm.K + 31) / 32 * 32) return PS_EUNSUPPORTED;
     if (dm.NB % t.c_split != 0) return PS_EUNSUPPORTED;
@@ -102,6 +105,7 @@ bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes)
 int kernel_variant(const Dims &dm, const ps_tile &t, const ShapeEntry &sh)
 {
     const int nb_split = dm.NB / t.c_split;
+    if (sh.stationary) return PS_KERNEL_STATIONARY_1X1;  // (tile_valid admits these shapes for nothing else)
     if (sh.launch_halo && halo_applies(dm, t, sh.halo_bytes)) return PS_KERNEL_PATCH_3X3;
     if (packs_taps(dm) && t.c_split == 1 && sh.launch_7x7p) return PS_KERNEL_PACKED_7X7;
     if (dm.R == dm.S && nb_split % (dm.R * dm.S) == 0) {
@@ -149,7 +153,8 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     a.out_bytes = (unsigned)((size_t)dm.M * dm.K * 4);
     LaunchFn fn = sh->launch;
     switch (kernel_variant(dm, t, *sh)) {
-    case PS_KERNEL_1X1: fn = sh->launch_1x1; break;
+    case PS_KERNEL_1X1:
+    case PS_KERNEL_STATIONARY_1X1: fn = sh->launch_1x1; break;
     case PS_KERNEL_3X3: fn = sh->launch_3x3; break;
     case PS_KERNEL_PATCH_3X3: fn = sh->launch_halo; break;
     case PS_KERNEL_PACKED_7X7:

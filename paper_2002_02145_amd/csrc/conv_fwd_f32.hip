@@ -1,6 +1,7 @@
 // fp32 kernel shapes of the batch-reduce-GEMM convolution and their launcher.
 #include "conv_fwd_kernel.h"
 #include "conv_fwd_f32_n16.h"
+#include "conv_fwd_f32_n16_kloop.h"
 
 namespace ps {
 
@@ -26,6 +27,7 @@ static const ShapeEntry kF32Shapes[] = {
     // 64 channels x MT pixels on 16x16x4 MFMA tiles: pixel tiles in steps of 16, for even division over the chip
     PS_F32_N16_SHAPE(48, 2), PS_F32_N16_SHAPE(48, 4), PS_F32_N16_SHAPE(96, 2), PS_F32_N16_SHAPE(96, 4),
     PS_F32_N16_SHAPE(176, 2), PS_F32_N16_SHAPE(176, 4),
+    PS_F32_N16_KLOOP_SHAPE(48), PS_F32_N16_KLOOP_SHAPE(96), PS_F32_N16_KLOOP_SHAPE(176),
 };
 
 const ShapeEntry *f32_shapes(int *count)

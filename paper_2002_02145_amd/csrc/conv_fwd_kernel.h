@@ -572,6 +572,7 @@ struct ShapeEntry {
     LaunchFn launch_7x7p; // R = S = 7, C <= 4: tap-packed
     LaunchFn launch_halo; // 3x3, stride 1, pad 1 with the input patch staged once per c-block (nullptr if none)
     int halo_bytes;       // capacity of that kernel's patch
+    int stationary;       // 1: pixels with all their input channels stay in LDS (1x1 filters, C = 64 only)
 };
 
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>

@@ -22,7 +22,7 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
 bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes);  // api.hip
@@ -60,6 +60,13 @@ bool baked_filter(const Dims &dm, int nb_split)
 {
     if (packs_taps(dm)) return nb_split == dm.NB;  // unsplit only
     return dm.R == dm.S && (dm.R == 1 || dm.R == 3) && nb_split % (dm.R * dm.S) == 0;
+}
+
+// The pixel-stationary fp32 kernels: 1x1 filters over exactly 4 c-blocks (everything a pixel needs fits in LDS next
+// to double-buffered filter slices), images of at least 16 pixels.
+bool stationary_applies(const Dims &dm)
+{
+    return dm.dtype == PS_F32 && dm.R == 1 && dm.S == 1 && dm.Cb == 4 && (long long)dm.P * dm.Q >= 16;
 }
 
 // batch elements one loop iteration of the kernel consumes (the 16-bit kernels group several per ring slot;
@@ -149,7 +156,14 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double clk_wg = (tiles_wave * (t.c_split > 1 && !with_ws ? 1900.0 : 1250.0) +
                            (sh.baked_only ? 200.0 * (t.mt / 16.0) : 0.0)) * waves_wg / 4.0;  // per SIMD
     double t_mfma;
-    if (f32) {
+    if (sh.stationary) {
+        // One workgroup walks over kt / 64 output tiles with its pixels resident: set-up and the first loads (all
+        // pixels, two filter slices; every workgroup of the launch asks at once) are paid once per launch, and a
+        // tile boundary costs the issue of its stores (measured 3.2 us, and 0.3 us per 176-pixel tile).
+        const double tiles = t.kt / 64.0;
+        const double clk_boundary = tiles * (150.0 + 90.0 * t.mt / 16.0);
+        t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + 7700.0 + per_cu * clk_boundary) / c.clock_hz;
+    } else if (f32) {
         t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + c.fill_clk + per_cu * clk_wg +
                   per_cu * (t.ring - 2) * 250.0) / c.clock_hz;  // a deeper ring takes longer to fill, per workgroup
     } else {
@@ -217,6 +231,7 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
         const long long n_mt = (dm.M + s.mt - 1) / s.mt;
         const long long base_wg = n_mt * ((dm.K + s.kt - 1) / s.kt);
         if (s.baked_only && !(dm.R == dm.S && (dm.R == 1 || dm.R == 3))) continue;
+        if (s.stationary && !stationary_applies(dm)) continue;
         for (int sp : splits) {
             if (dm.NB % sp != 0) continue;
             if (s.baked_only && sp > 1) continue;  // no atomic epilogue in these kernels

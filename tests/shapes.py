@@ -15,4 +15,6 @@ EDGE_SHAPES = [
     ConvShape(1, 80, 3, 3, 96, 1, 1, 1, 0, "five_blocks_prime_batch"),  # batch-reduce length 5
     ConvShape(2, 4, 9, 10, 16, 7, 7, 1, 3, "7x7_C4_stride1"),           # tap-packed path with all 4 lanes real
     ConvShape(1, 5, 9, 9, 32, 7, 7, 2, 3, "7x7_C5_not_packed"),         # one channel too many for tap packing
+    ConvShape(3, 64, 9, 7, 256, 1, 1, 1, 0, "1x1_64to256_tiles_cross_images"),  # pixel-stationary kernels, ragged tail
+    ConvShape(2, 50, 10, 10, 512, 1, 1, 2, 0, "1x1_C50_K512_stride2"),  # the same with zero lanes, two channel groups
 ]

@@ -66,6 +66,20 @@ def test_fused_matches_oracle_on_every_tile(oracle_lib, shape, dtype, out_dtype)
         _check(oracle_lib, got, shape, x, w, b, relu, out_dtype, TOL[dtype])
 
 
+@pytest.mark.parametrize("out_dtype", [ps.PS_F32, ps.PS_BF16], ids=["out_fp32", "out_bf16"])
+def test_fused_pixel_stationary_tiles(oracle_lib, out_dtype):
+    """The kernels that keep a tile's pixels in LDS and walk over four output tiles have their own fused stores."""
+    shape = wl.ConvShape(3, 64, 9, 7, 512, 1, 1, 1, 0, "1x1_64to512")
+    x, w = wl.uniform_pm1(shape, 22)
+    bias = np.random.default_rng(5).standard_normal(shape.K).astype(np.float32)
+    tiles = [t for t in all_tiles(shape, ps.PS_F32) if ps.KERNEL_NAMES[ps.ps_tile_kernel(ps.ConvDesc.of(shape), t)] == "1x1 pixel-stationary"]
+    assert len(tiles) >= 3
+    for i, t in enumerate(tiles):
+        relu, b = bool(i % 2), (bias if i % 3 != 1 else None)
+        got, _, _ = _run(shape, x, w, ps.PS_F32, t, b, relu, out_dtype)
+        _check(oracle_lib, got, shape, x, w, b, relu, out_dtype, TOL[ps.PS_F32])
+
+
 @pytest.mark.parametrize("dtype", [ps.PS_F32, ps.PS_BF16], ids=["fp32", "bf16"])
 def test_fused_bf16_output_is_exact_on_integers(oracle_lib, dtype):
     """Small-integer tensors make every sum exact, so the stored bf16 must be the correctly rounded value (many sums
