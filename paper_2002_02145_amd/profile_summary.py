@@ -23,7 +23,8 @@ def kernel_source_digest(dtype: str = "f32") -> str:
     """Digest of the kernel sources of `dtype` ("f32" or "bf16"); which tile and which inner loop run is recorded
     beside it."""
     h = hashlib.sha256()
-    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip", "conv_fwd_bf16_halo.h" if dtype == "bf16" else "conv_fwd_f32_n16.h"]
+    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip"] + (["conv_fwd_bf16_halo.h"] if dtype == "bf16" else
+                                                            ["conv_fwd_f32_n16.h", "conv_fwd_f32_n16_kloop.h"])
     for f in files:
         with open(os.path.join(HERE, "csrc", f), "rb") as fh:
             h.update(fh.read())
