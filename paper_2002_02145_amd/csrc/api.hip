@@ -124,6 +124,7 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     ConvArgs a;
     a.in = in; a.wt = wt; a.out = out;
     a.bias = bias; a.epi = epi;
+    a.cin = dm.C;
     a.H = dm.H; a.W = dm.W; a.Cb = dm.Cb; a.Kb = dm.Kb; a.R = dm.R; a.S = dm.S;
     a.stride = dm.stride; a.pad = dm.pad; a.Q = dm.Q;
     a.PQ = dm.P * dm.Q;

@@ -52,6 +52,7 @@ struct ConvArgs {
     const void *wt;
     float *out;
     int H, W, Cb, Kb, R, S, stride, pad, Q;
+    int cin;       // input channels before padding to whole 16-blocks
     int PQ;        // P*Q
     int M;         // N*P*Q, flattened output pixels
     int NB;        // Cb*R*S, batch-reduce length
@@ -297,8 +298,9 @@ struct F32Shape {
 // (e / NTAP) are compile-time after unrolling, per-lane offsets come precomputed per tap, everything else is
 // scalar arithmetic.  An element beyond the range gets descriptors of size 0, i.e. reads zeros.
 // (A __device__ function rather than a lambda of the kernel: lambdas are also compiled for the host,
-// where buffer descriptors cannot be built.)
-template <class Sh, int NBUF, int NTAP, int APW, int WPW, bool PACK4>
+// where buffer descriptors cannot be built.  TAG only gives kernels that agree in every other argument an
+// instance of their own.)
+template <class Sh, int NBUF, int NTAP, int APW, int WPW, bool PACK4, int TAG = 0>
 __device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, const unsigned (&vtap)[APW][NTAP],
                                                const int (&wsoff)[WPW], const bool (&wok)[WPW],
                                                const unsigned (&vw)[2], int wave, int slot, int e, int b0, int cb0)
@@ -342,7 +344,12 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
     // adjacent taps (4 taps x 4 channels = the 16 reduction lanes) instead of 16 channels of one tap, so a
     // 7x7 filter takes 7 rows x 2 tap groups = 14 elements instead of 49.  Pixels and filter rows are gathered
     // accordingly from the ordinary blocked tensors: only the per-lane load offsets differ.
-    constexpr bool PACK4 = SIDE == 7;
+    constexpr bool PACK4 = SIDE == 7 || SIDE == 37;
+    // SIDE = 37: the same with at most 3 input channels.  Lane 3 of every tap's 4-channel group is then zero padding,
+    // and with the reduction index permuted as below it is MFMA steps 3 and 7 that would multiply it: they are
+    // left out, a quarter of the matrix-core work.
+    constexpr bool SKIP_C3 = SIDE == 37;
+    constexpr int FS = PACK4 ? 7 : SIDE;  // filter side
     constexpr int TAPS = PACK4 ? 14 : SIDE * SIDE;
     using Sh = F32Shape<KT, MT, WK, WM, NBUF>;
     constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
@@ -435,10 +442,10 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
             for (int t = 0; t < TAPS; ++t) {
                 // ordinary: tap (r, sx), this lane fetches chunk `gchunk` of the pixel's 16 channels;
                 // tap-packed: row r, taps 4g .. 4g+3, this lane fetches channels 0..3 of tap 4g + gchunk
-                const int r = PACK4 ? t / 2 : t / SIDE;
-                const int sx = PACK4 ? (t % 2) * 4 + gchunk : t % SIDE;
+                const int r = PACK4 ? t / 2 : t / FS;
+                const int sx = PACK4 ? (t % 2) * 4 + gchunk : t % FS;
                 const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W) &
-                                (sx < SIDE);
+                                (sx < FS);
                 vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 64 + (PACK4 ? 0 : gchunk * 16)) : kOobOffset;
             }
 #pragma unroll
@@ -500,12 +507,14 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 
     auto mfmas = [&](int par) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
+        for (int t = 0; t < 8; ++t) {
+            if (SKIP_C3 && (t & 3) == 3) continue;  // channel 3 of both taps of this lane's half: zeros
 #pragma unroll
             for (int tk = 0; tk < TK; ++tk)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
                     acc[tk][tm] = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[par][tk][t], pf[par][tm][t], acc[tk][tm], 0, 0, 0);
+        }
     };
 
     // ---- pipeline ---------------------------------------------------------------------------
@@ -516,7 +525,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         int cb0 = b_begin / TAPS;
 #pragma unroll
         for (int e = 0; e < D; ++e)
-            issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+            issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4, SIDE>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
         wait_vm_and_barrier<(D - 1) * LPE>();
         read_frags(0, 0);
         for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
@@ -524,7 +533,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
             for (int u = 0; u < U; ++u) {
                 wait_vm_and_barrier<(D - 2) * LPE>();
                 read_frags((u + 1) % NBUF, (u + 1) % 2);
-                issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,
+                issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4, SIDE>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,
                                                          b0, cb0);
                 mfmas(u % 2);
                 // order within the iteration: after each of the first MFMAs one LDS read and one load, so
@@ -581,9 +590,19 @@ void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
     hipLaunchKernelGGL((conv_fwd_f32_kernel<KT, MT, WK, WM, NBUF, SIDE>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
 
+// tap-packed 7x7: with at most 3 real input channels the kernel that leaves out the zero lane's MFMA steps
+template <int KT, int MT, int WK, int WM, int NBUF>
+void launch_f32_packed(const ConvArgs &a, unsigned grid, hipStream_t st)
+{
+    if (a.cin <= 3)
+        launch_f32<KT, MT, WK, WM, NBUF, 37>(a, grid, st);
+    else
+        launch_f32<KT, MT, WK, WM, NBUF, 7>(a, grid, st);
+}
+
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
     {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES, 1,                   \
      &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
-     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32<KT, MT, WK, WM, NBUF, 7>, nullptr, 0}
+     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32_packed<KT, MT, WK, WM, NBUF>, nullptr, 0}
 
 }  // namespace ps

@@ -133,7 +133,9 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double per_simd = std::ceil(per_cu * waves_wg / 4.0);
     const double mfma_clk = dm.dtype == PS_F32 ? 64.0 * 8.0 : 32.0;  // per 32x32 tile per batch element
     const double eff = baked ? c.steady_eff_baked : c.steady_eff_general[dm.dtype == PS_F32 ? 0 : 1];
-    const double clk_wave = tiles_wave * mfma_clk * nb_pad / eff;
+    // tap-packed 7x7 over at most 3 channels: the MFMA steps of the zero lane are left out
+    const double lane_skip = packs_taps(dm) && baked && dm.C <= 3 ? 0.75 : 1.0;
+    const double clk_wave = tiles_wave * mfma_clk * lane_skip * nb_pad / eff;
     // per batch element a wave also pays a barrier and the issue of its loads and LDS reads; with a
     // single resident wave per SIMD nothing hides that
     const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
