@@ -160,7 +160,7 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     case PS_KERNEL_PATCH_3X3: fn = sh->launch_halo; break;
     case PS_KERNEL_PACKED_7X7:
         fn = sh->launch_7x7p;
-        a.nb_split = 14;  // 7 filter rows x 2 groups of 4 taps; a.NB stays 49 for filter addressing
+        a.nb_split = 13;  // 49 taps, four per batch element; a.NB stays 49 for filter addressing
         break;
     default: break;
     }

@@ -323,9 +323,9 @@ __device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, con
         const __amdgpu_buffer_rsrc_t rwt_v = make_rsrc(a.wt, (valid & wok[i]) ? a.wt_bytes : 0u);
         char *dst = (Sh::WBLK % NW == 0 || blk < Sh::WBLK) ? sbase + Sh::A_BYTES + blk * Sh::WPITCH
                                                            : lds + NBUF * Sh::SLOT;
-        // tap-packed mode: filter row r = tap / 2 of the 7x7 filter, per-lane offsets pick the taps 4g .. 4g+3
-        const int wso = PACK4 ? wsoff[i] + (tap / 2) * 7 * 1024 : wsoff[i] + ((b0 + e) << 10);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt_v, (lds_ptr_t)dst, 16, vw[PACK4 ? tap % 2 : 0], wso, 0, 0);
+        // tap-packed mode: the blocks of taps 4*tap .. 4*tap+3, per-lane offsets pick tap and channel row
+        const int wso = PACK4 ? wsoff[i] + tap * 4 * 1024 : wsoff[i] + ((b0 + e) << 10);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rwt_v, (lds_ptr_t)dst, 16, vw[PACK4 && tap == NTAP - 1 ? 1 : 0], wso, 0, 0);
     }
 }
 
@@ -341,16 +341,16 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 {
     // SIDE = 7 is the tap-packed mode for inputs with at most 4 channels (one c-block whose lanes 4..15 are
     // zero padding, e.g. an RGB network stem): a batch element then holds channels 0..3 of four horizontally
-    // adjacent taps (4 taps x 4 channels = the 16 reduction lanes) instead of 16 channels of one tap, so a
-    // 7x7 filter takes 7 rows x 2 tap groups = 14 elements instead of 49.  Pixels and filter rows are gathered
-    // accordingly from the ordinary blocked tensors: only the per-lane load offsets differ.
+    // consecutive taps of the row-major tap sequence (4 taps x 4 channels = the 16 reduction lanes) instead of 16
+    // channels of one tap, so a 7x7 filter takes ceil(49 / 4) = 13 elements instead of 49.  Pixels and filter blocks
+    // are gathered accordingly from the ordinary blocked tensors: only the per-lane load offsets differ.
     constexpr bool PACK4 = SIDE == 7 || SIDE == 37;
     // SIDE = 37: the same with at most 3 input channels.  Lane 3 of every tap's 4-channel group is then zero padding,
     // and with the reduction index permuted as below it is MFMA steps 3 and 7 that would multiply it: they are
     // left out, a quarter of the matrix-core work.
     constexpr bool SKIP_C3 = SIDE == 37;
     constexpr int FS = PACK4 ? 7 : SIDE;  // filter side
-    constexpr int TAPS = PACK4 ? 14 : SIDE * SIDE;
+    constexpr int TAPS = PACK4 ? 13 : SIDE * SIDE;
     using Sh = F32Shape<KT, MT, WK, WM, NBUF>;
     constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
     constexpr int APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
@@ -441,11 +441,13 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 #pragma unroll
             for (int t = 0; t < TAPS; ++t) {
                 // ordinary: tap (r, sx), this lane fetches chunk `gchunk` of the pixel's 16 channels;
-                // tap-packed: row r, taps 4g .. 4g+3, this lane fetches channels 0..3 of tap 4g + gchunk
-                const int r = PACK4 ? t / 2 : t / FS;
-                const int sx = PACK4 ? (t % 2) * 4 + gchunk : t % FS;
+                // tap-packed: element t holds taps 4t .. 4t+3 of the sequence r*7 + s, this lane fetches channels
+                // 0..3 of tap 4t + gchunk (x * 37 >> 8 = x / 7 for x < 56)
+                const int tapidx = 4 * t + gchunk;
+                const int r = PACK4 ? (tapidx * 37) >> 8 : t / FS;
+                const int sx = PACK4 ? tapidx - 7 * r : t % FS;
                 const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W) &
-                                (sx < FS);
+                                (!PACK4 || tapidx < 49);
                 vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 64 + (PACK4 ? 0 : gchunk * 16)) : kOobOffset;
             }
 #pragma unroll
@@ -456,12 +458,13 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         }
     }
     // per-lane offset of a filter load inside its 1 KB block: lane*16 normally; tap-packed, LDS row
-    // c' = lane/4 = 4*j + c is row c of the block of tap 4g + j
+    // c' = lane/4 = 4*j + c is row c of the block of tap 4t + j (blocks follow the tap sequence; [1]: the last
+    // element, where only tap 48 exists)
     unsigned vw[2];
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
-        const int cp = lane >> 2, j = cp >> 2, c = cp & 3, sx = 4 * g + j;
-        vw[g] = !PACK4 ? (unsigned)lane << 4 : sx < 7 ? (unsigned)(sx * 1024 + c * 64 + (lane & 3) * 16) : kOobOffset;
+        const int cp = lane >> 2, j = cp >> 2, c = cp & 3;
+        vw[g] = !PACK4 ? (unsigned)lane << 4 : (g == 0 || j == 0) ? (unsigned)(j * 1024 + c * 64 + (lane & 3) * 16) : kOobOffset;
     }
     // ---- reader bookkeeping -------------------------------------------------------------
     int paddr[TM], waddr[TK];
@@ -531,6 +534,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if (PACK4 && u >= TAPS) break;  // a tap-packed range is exactly TAPS elements (an odd number)
                 wait_vm_and_barrier<(D - 2) * LPE>();
                 read_frags((u + 1) % NBUF, (u + 1) % 2);
                 issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4, SIDE>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,

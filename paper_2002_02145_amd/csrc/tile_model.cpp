@@ -78,7 +78,7 @@ int group_of(const Dims &dm, const ShapeInfo &sh, int nb_split)
 }
 
 // batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples
-int logical_elems(const Dims &dm, int nb_split) { return baked_filter(dm, nb_split) && packs_taps(dm) ? 14 : nb_split; }
+int logical_elems(const Dims &dm, int nb_split) { return baked_filter(dm, nb_split) && packs_taps(dm) ? 13 : nb_split; }
 
 int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
 {
@@ -89,8 +89,8 @@ int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
         unit = ring * g;
         if (g == 3) unit = ring % 3 == 0 ? ring * 3 : ring * 9;  // lcm(ring, 3) iterations of 3 elements
     } else if (baked_filter(dm, nb_split)) {
-        const int taps = packs_taps(dm) ? 14 : dm.R * dm.S;
-        if (packs_taps(dm)) nb_split = 14;  // 7 rows x 2 groups of 4 taps replace the 49 taps
+        if (packs_taps(dm)) return 13;  // 49 taps, four per element, in one pass of exactly 13 iterations
+        const int taps = dm.R * dm.S;
         int g = ring, h = taps;
         while (h) { const int r = g % h; g = h; h = r; }
         unit = ring / g * taps;
