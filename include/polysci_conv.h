@@ -144,6 +144,12 @@ double ps_tile_cost_ws_us(const ps_conv_desc *d, const ps_tile *t);
 int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us);
 /* Same for ps_conv2d_fwd_ws: only candidates whose workspace fits in `workspace_bytes` compete. */
 int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *best, double *modelled_us);
+/* The paper's protocol in full (Section 4.2: rank the n variants, run the top k on the target, keep the fastest):
+ * writes the k candidates with the lowest modelled time, best first, to tiles[0..] (host memory, room for k entries;
+ * modelled_us may be NULL, else room for k values) under the rules of ps_tile_select_ws, and returns how many were
+ * written (fewer than k if the layer has fewer candidates), or a negative ps_status.  tiles[0] is the tile
+ * ps_tile_select_ws returns.  Timing the k tiles is the caller's part (paper_2002_02145_amd.autotune.run_top_k). */
+int ps_tile_rank_ws(const ps_conv_desc *d, size_t workspace_bytes, int k, ps_tile *tiles, double *modelled_us);
 
 /* Which inner loop the library runs for tile `t` on `d` (for reports and tests): the loop with a runtime filter size,
  * the loops with a 1x1 or 3x3 filter baked in, the 7x7 loop that packs four taps of up to four channels into one

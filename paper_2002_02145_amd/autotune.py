@@ -100,6 +100,19 @@ def sweep(shape: wl.ConvShape, dtype: int = ps.PS_F32, min_ms: float = 20.0, col
     }
 
 
+def run_top_k(desc: ps.ConvDesc, k: int, workspace: torch.Tensor, sets=None, min_ms: float = 5.0):
+    """The paper's selection protocol (Section 4.2): the model ranks all variants, the best k are run on the target
+    and the fastest is kept.  Returns (tile, measured us, [(tile, modelled us, measured us), ...]); k = 1 is the
+    library's own pick.  `workspace` is what the caller lends for split reductions (may be a 4-element tensor)."""
+    es = 4 if desc.dtype == ps.PS_F32 else 2
+    sets = sets or _buffers(desc, es)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    ranked = ps.ps_tile_rank_ws(desc, ws_bytes, k)
+    rows = [(t, model_us, time_tile(desc, t, sets, min_ms=min_ms, workspace=workspace)) for t, model_us in ranked]
+    best = min(rows, key=lambda r: r[2])
+    return best[0], best[2], rows
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__)
     ap.add_argument("--layers", default="sweep", help="sweep | cfg1 | cfg2 | cfg3a | cfg3b | comma list of layer names")

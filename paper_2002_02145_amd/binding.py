@@ -108,6 +108,7 @@ def _load() -> ctypes.CDLL:
         "ps_tile_kernel": (ctypes.c_int, [dp, tp]),
         "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
+        "ps_tile_rank_ws": (ctypes.c_int, [dp, ctypes.c_size_t, ctypes.c_int, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_tile_count": (ctypes.c_int, [dp]),
         "ps_tile_get": (ctypes.c_int, [dp, ctypes.c_int, tp]),
         "ps_tile_valid": (ctypes.c_int, [dp, tp]),
@@ -243,6 +244,14 @@ def ps_tile_select_ws(desc: ConvDesc, workspace_bytes: int) -> tuple[Tile, float
     _check(lib.ps_tile_select_ws(ctypes.byref(desc), int(workspace_bytes), ctypes.byref(t), ctypes.byref(us)),
            "ps_tile_select_ws")
     return t, us.value
+
+
+def ps_tile_rank_ws(desc: ConvDesc, workspace_bytes: int, k: int) -> list[tuple[Tile, float]]:
+    tiles, us = (Tile * k)(), (ctypes.c_double * k)()
+    n = lib.ps_tile_rank_ws(ctypes.byref(desc), int(workspace_bytes), int(k), tiles, us)
+    if n < 0:
+        raise PsError(n, "ps_tile_rank_ws")
+    return [(Tile(tiles[i].kt, tiles[i].mt, tiles[i].ring, tiles[i].c_split, tiles[i].raster), us[i]) for i in range(n)]
 
 
 def ps_tile_count(desc: ConvDesc) -> int:

@@ -15,6 +15,7 @@
 // All constants are per-chip figures, not fitted per layer.
 #include <algorithm>
 #include <cmath>
+#include <utility>
 #include <vector>
 
 #include "ps_internal.h"
@@ -329,6 +330,29 @@ static int select_best(const ps_conv_desc *d, bool with_ws, size_t ws_bytes, ps_
     *best = c[bi].t;
     if (modelled_us) *modelled_us = bu;
     return PS_OK;
+}
+
+extern "C" int ps_tile_rank_ws(const ps_conv_desc *d, size_t workspace_bytes, int k, ps_tile *tiles, double *modelled_us)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (k <= 0 || !tiles) return PS_EINVAL;
+    std::vector<Cand> c;
+    enumerate(dm, c);
+    std::vector<std::pair<double, int>> order;
+    for (size_t i = 0; i < c.size(); ++i) {
+        if (c[i].t.c_split > 1 && (size_t)c[i].t.c_split * (size_t)dm.M * dm.K * 4 > workspace_bytes) continue;
+        order.emplace_back(model_cost(dm, c[i].t, c[i].sh, true), (int)i);
+    }
+    if (order.empty()) return PS_EUNSUPPORTED;
+    std::stable_sort(order.begin(), order.end());  // ties keep the enumeration order, as the k = 1 pick does
+    const int n = std::min<int>(k, (int)order.size());
+    for (int j = 0; j < n; ++j) {
+        tiles[j] = c[order[j].second].t;
+        if (modelled_us) modelled_us[j] = order[j].first;
+    }
+    return n;
 }
 
 extern "C" int ps_tile_select(const ps_conv_desc *d, ps_tile *best, double *modelled_us)

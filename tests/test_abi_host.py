@@ -90,6 +90,14 @@ def test_tile_enumerator_and_model(ps):
         assert bw.c_split == 1                       # no workspace: only unsplit tiles compete
         bw, usw = ps.ps_tile_select_ws(d, 1 << 40)
         assert usw == pytest.approx(min(ps.ps_tile_cost_ws_us(d, t) for t in tiles))
+        # rank n, run top k: the k lowest modelled times, best first, the first being the k = 1 pick
+        ranked = ps.ps_tile_rank_ws(d, 1 << 40, 5)
+        assert len(ranked) == min(5, n) and ranked[0][0].as_tuple() == bw.as_tuple()
+        assert [u for _, u in ranked] == sorted(u for _, u in ranked)
+        assert [u for _, u in ranked] == pytest.approx(sorted(ps.ps_tile_cost_ws_us(d, t) for t in tiles)[:len(ranked)])
+        assert all(u == pytest.approx(ps.ps_tile_cost_ws_us(d, t)) for t, u in ranked)
+        assert len(ps.ps_tile_rank_ws(d, 1 << 40, n + 7)) == n
+        assert all(t.c_split == 1 for t, _ in ps.ps_tile_rank_ws(d, 0, 3))
         best, us = ps.ps_tile_select(d)
         costs = [ps.ps_tile_cost_us(d, t) for t in tiles]
         assert us == pytest.approx(min(costs))

@@ -29,3 +29,20 @@ def test_model_pick_within_ten_percent_of_sweep_best_fp32(name):
     assert pick_us <= 1.10 * best_us, f"{name}: pick {r['pick']} {pick_us:.1f} us vs best {r['best']} {best_us:.1f} us"
     # sanity of the distribution the paper plots: the worst variant is clearly slower than the best
     assert r["worst_us"] >= best_us
+
+
+def test_run_top_k_keeps_the_fastest_of_the_models_best():
+    """Section 4.2's protocol end to end: the k best-ranked tiles are timed, the fastest is returned; k = 1 is the
+    library's pick."""
+    import torch
+    from paper_2002_02145_amd import autotune, binding as ps
+    shape = {l.name: l for l in wl.resnet50_layers()}["1x1_1024to256_14"]
+    desc = ps.ConvDesc.of(shape)
+    ws = torch.empty((64 << 20) // 4, device="cuda")
+    pick, _ = ps.ps_tile_select_ws(desc, 64 << 20)
+    tile, us, rows = autotune.run_top_k(desc, 3, ws)
+    assert len(rows) == 3 and rows[0][0].as_tuple() == pick.as_tuple()
+    assert us == min(r[2] for r in rows) and tile.as_tuple() in {r[0].as_tuple() for r in rows}
+    t1, us1, rows1 = autotune.run_top_k(desc, 1, ws)
+    assert t1.as_tuple() == pick.as_tuple() and len(rows1) == 1
+    assert us <= 1.05 * us1          # running more candidates never loses (up to timing noise)
