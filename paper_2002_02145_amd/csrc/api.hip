@@ -71,7 +71,9 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.ring);
     if (!sh) return PS_EUNSUPPORTED;
     // shapes without a loop for a runtime filter size and without an atomic epilogue: 1x1 and 3x3, unsplit
-    if (!sh->launch && !(t.c_split == 1 && dm.R == dm.S && (dm.R == 1 || dm.R == 3))) return PS_EUNSUPPORTED;
+    if (!sh->launch && !(t.c_split == 1 && ((dm.R == dm.S && (dm.R == 1 || dm.R == 3)) ||
+                                            (packs_taps(dm) && dm.C <= 3 && sh->launch_7x7p))))
+        return PS_EUNSUPPORTED;
     // pixel-stationary shapes: 1x1 filters over exactly 4 c-blocks, images of at least 16 pixels
     if (sh->stationary && !(dm.R == 1 && dm.S == 1 && t.c_split == 1 && dm.Cb == 4 && dm.P * dm.Q >= 16))
         return PS_EUNSUPPORTED;

@@ -50,8 +50,13 @@ struct N16Shape {
 template <int MT, int NBUF, int SIDE, bool FUSED>
 __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
 {
-    static_assert(SIDE == 1 || SIDE == 3, "filter sizes with a baked loop");
-    constexpr int TAPS = SIDE * SIDE;
+    // SIDE = 37: 7x7 filter over at most 3 input channels, tap-packed as in conv_fwd_kernel.h (a batch element holds
+    // 4 consecutive taps x [c0 c1 c2 0]); chunk g of a pixel is then tap g and MFMA step t is channel t, so step 3
+    // would only multiply the padding lane and is left out.
+    static_assert(SIDE == 1 || SIDE == 3 || SIDE == 37, "filter sizes with a baked loop");
+    constexpr bool PACKED = SIDE == 37;
+    constexpr int TAPS = PACKED ? 13 : SIDE * SIDE;
+    constexpr int STEPS = PACKED ? 3 : 4;
     using Sh = N16Shape<MT, NBUF, FUSED>;
     constexpr int NW = Sh::NW, NT = Sh::NT, APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
     constexpr int U = NBUF / ct_gcd(NBUF, TAPS) * TAPS;
@@ -81,9 +86,12 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
         const int poff = (n * a.Cb * a.H + h0) * a.W + w0;
 #pragma unroll
         for (int t = 0; t < TAPS; ++t) {
-            const int r = t / SIDE, sx = t % SIDE;
-            const bool ok = ((unsigned)(h0 + r) < (unsigned)a.H) & ((unsigned)(w0 + sx) < (unsigned)a.W);
-            vtap[i][t] = ok ? (unsigned)((poff + r * a.W + sx) * 64 + (lane & 3) * 16) : kOobOffset;
+            // packed: this lane fetches channels 0..3 of tap 4t + lane%4 of the sequence r*7 + s (x*37 >> 8 = x/7)
+            const int tapidx = 4 * t + (lane & 3);
+            const int r = PACKED ? (tapidx * 37) >> 8 : t / SIDE, sx = PACKED ? tapidx - 7 * r : t % SIDE;
+            const bool ok = ((unsigned)(h0 + r) < (unsigned)a.H) & ((unsigned)(w0 + sx) < (unsigned)a.W) &
+                            (!PACKED || tapidx < 49);
+            vtap[i][t] = ok ? (unsigned)((poff + r * a.W + sx) * 64 + (PACKED ? 0 : (lane & 3) * 16)) : kOobOffset;
         }
     }
     int wsoff[WPW];
@@ -94,7 +102,10 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     // 4q .. 4q+3 with t = lane/16, g = (lane/4)%4, q = lane%4, so that at MFMA step t the four lane groups read four
     // adjacent 64-byte rows (all banks) instead of rows 256 bytes apart (one bank group, four-way conflict).
     const unsigned wsrc = (unsigned)((4 * ((lane >> 2) & 3) + (lane >> 4)) * 64 + (lane & 3) * 16);
-    const unsigned vw[2] = {wsrc, wsrc};
+    // packed: position (t, g, q) takes row t (channel) of the block of tap 4e + g; channel 3 is never multiplied;
+    // [1] is for the last element, where only tap 48 exists
+    const unsigned wpk = (lane >> 4) == 3 ? kOobOffset : (unsigned)(((lane >> 2) & 3) * 1024 + (lane >> 4) * 64 + (lane & 3) * 16);
+    const unsigned vw[2] = {PACKED ? wpk : wsrc, PACKED ? (((lane >> 2) & 3) == 0 ? wpk : kOobOffset) : wsrc};
 
     // ---- reader -------------------------------------------------------------------------------------
     const int paddr = l16 * 64 + g * 16;                                  // + tile * 1024
@@ -119,18 +130,19 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     int cb0 = b_begin / TAPS;
 #pragma unroll
     for (int e = 0; e < D; ++e)
-        issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, false>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+        issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, PACKED>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
     wait_vm_and_barrier<(D - 1) * LPE>();
     PS_N16_READ(0, 0)
     for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            if (PACKED && u >= TAPS) break;  // a tap-packed range is exactly TAPS elements (an odd number)
             wait_vm_and_barrier<(D - 2) * LPE>();
             PS_N16_READ((u + 1) % NBUF, (u + 1) % 2)
-            issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, false>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF,
+            issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, PACKED>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF,
                                                                              u + NBUF, b0, cb0);
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < STEPS; ++t)
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[u % 2][t], pf[u % 2][j][t], acc[j], 0, 0, 0);
@@ -251,9 +263,9 @@ void launch_f32_n16(const ConvArgs &a, unsigned grid, hipStream_t st)
 }
 
 // No loop with a runtime filter size and no atomic epilogue: the enumerator offers these shapes for 1x1 and 3x3
-// filters, unsplit or with workspace planes.
+// filters and for 7x7 filters over at most 3 channels, unsplit.
 #define PS_F32_N16_SHAPE(MT, NBUF)                                                                  \
     {PS_F32, 64, MT, NBUF, 256, N16Shape<MT, NBUF>::LDS_BYTES, 1, nullptr, &launch_f32_n16<MT, NBUF, 1>, \
-     &launch_f32_n16<MT, NBUF, 3>, nullptr, nullptr, 0}
+     &launch_f32_n16<MT, NBUF, 3>, &launch_f32_n16<MT, NBUF, 37>, nullptr, 0}
 
 }  // namespace ps

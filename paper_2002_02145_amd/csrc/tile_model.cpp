@@ -233,7 +233,8 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
         if (s.mt > 64 && s.mt >= 2 * dm.M) continue;
         const long long n_mt = (dm.M + s.mt - 1) / s.mt;
         const long long base_wg = n_mt * ((dm.K + s.kt - 1) / s.kt);
-        if (s.baked_only && !(dm.R == dm.S && (dm.R == 1 || dm.R == 3))) continue;
+        if (s.baked_only && !((dm.R == dm.S && (dm.R == 1 || dm.R == 3)) || (packs_taps(dm) && dm.C <= 3 && !s.stationary)))
+            continue;
         if (s.stationary && !stationary_applies(dm)) continue;
         for (int sp : splits) {
             if (dm.NB % sp != 0) continue;

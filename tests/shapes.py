@@ -17,5 +17,6 @@ EDGE_SHAPES = [
     ConvShape(1, 5, 9, 9, 32, 7, 7, 2, 3, "7x7_C5_not_packed"),         # one channel too many for tap packing
     ConvShape(3, 64, 9, 7, 256, 1, 1, 1, 0, "1x1_64to256_tiles_cross_images"),  # pixel-stationary kernels, ragged tail
     ConvShape(2, 50, 10, 10, 512, 1, 1, 2, 0, "1x1_C50_K512_stride2"),  # the same with zero lanes, two channel groups
+    ConvShape(2, 3, 20, 17, 64, 7, 7, 2, 3, "stem_like_K64"),           # tap-packed 7x7 in the 16x16-tile kernels too
     ConvShape(1, 64, 5, 5, 240, 1, 1, 1, 1, "1x1_64to240_pad1"),        # ... last channel block missing, padded border
 ]

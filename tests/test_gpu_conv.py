@@ -51,7 +51,7 @@ def test_every_candidate_tile_matches_oracle(shape):
         assert oracle.normalised_error(got, out, mag) <= TOL[dtype]
 
 
-@pytest.mark.parametrize("shape", EDGE_SHAPES[:5] + [s for s in EDGE_SHAPES if s.name.startswith("1x1_64to256")],
+@pytest.mark.parametrize("shape", EDGE_SHAPES[:5] + [s for s in EDGE_SHAPES if s.name.startswith(("1x1_64to256", "stem_like_K64"))],
                          ids=lambda s: s.name)
 def test_integer_inputs_reproduce_exact_result(shape):
     from gpu_util import run_conv, all_tiles
