@@ -59,9 +59,11 @@ typedef struct {
 /* One point of the outer-loop variant space (Section 4.2: tiling and interchange of the
  * loops around the microkernel, with varied tile sizes), in GPU terms:
  *   kt      output channels per workgroup tile (32, 64, 128 or 256)
- *   mt      output pixels per workgroup tile, counted in the flattened (n, p, q) order
+ *   mt      output pixels per workgroup tile, counted in the flattened (n, p, q) order (32 ... 256 in steps of 32
+ *           on 32x32 MFMA tiles; 48, 96 or 176 on 16x16 MFMA tiles, fp32 only: kt = 64, or kt = 256 for the 1x1
+ *           kernels that keep the pixels in LDS and walk over four 64-channel tiles)
  *   ring    batch-reduce elements (c-block, r, s) resident in the LDS ring, i.e. how far ahead of the
- *           matrix cores the global loads run (2 or 4)
+ *           matrix cores the global loads run (2, 4 or 8)
  *   c_split workgroups that share one output tile, each reducing a contiguous slice of the
  *           (c-block, r, s) range; > 1 accumulates with atomic adds into a cleared output
  *   raster  launch order of tiles: 0 = output-channel tiles fastest, 1 = pixel tiles fastest
