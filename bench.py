@@ -234,6 +234,19 @@ def main(argv=None) -> int:
                                                                            tile.kt, tile.mt, tile.ring),
                  "kernel_us": round(kernel_ms * 1e3, 2), "isolated_launch_us": round(each_ms * 1e3, 2),
                  "launches_per_step": 1 if tile.c_split == 1 else 2, "flop_per_launch": shape.flops})
+    # what the matrix cores of this device sustain with no operand traffic at all (context for the published peak)
+    sink = torch.zeros(1024, dtype=torch.float32, device=dev)
+    probe_iters = 2000 if a.dtype == "f32" else 4000
+    for _ in range(3):
+        probe_flop = ps.ps_probe_mfma(dtype, probe_iters, sink)
+    torch.cuda.synchronize()
+    pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pe0.record(torch.cuda.current_stream())
+    for _ in range(10):
+        ps.ps_probe_mfma(dtype, probe_iters, sink)
+    pe1.record(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    probe_tflops = probe_flop * 10 / (pe0.elapsed_time(pe1) * 1e-3) * 1e-12
     line = {
         "metric": "conv fwd GFLOP/s (2*N*K*P*Q*C*R*S/t), 1 GPU",
         "value": round(gflops, 1),
@@ -254,6 +267,7 @@ def main(argv=None) -> int:
         "cold": {"us": round(cold_ms * 1e3, 2), "GFLOP/s": round(shape.flops / (cold_ms * 1e-3) * 1e-9, 1),
                  "buffer_sets": n_sets, "bytes_rotated": n_sets * pair_bytes},
         "frac_mfma_peak": round(gflops * 1e-3 / peak, 4),
+        "mfma_only_loop_TFLOP/s": round(probe_tflops, 1),   # ps_probe_mfma: no LDS or memory traffic
         "roofline": roof,
         "cpu_baseline": cpu,
         "checked_against_oracle": checked,

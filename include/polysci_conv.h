@@ -168,6 +168,13 @@ typedef enum {
 } ps_kernel_variant;
 int ps_tile_kernel(const ps_conv_desc *d, const ps_tile *t);
 
+/* Measurement aid for reports (no part of the method): launches a loop of `iters` x 32 independent MFMAs per wave
+ * of the given element type (fp32: 16x16x4, bf16: 32x32x16) on 16 waves per compute unit, with no operand traffic,
+ * and writes the FLOP it performs to *flop (host pointer, may be NULL).  Timed by the caller with events on `stream`,
+ * it gives the rate the matrix cores of this device sustain, to put next to the published peak.  `sink` is a device
+ * buffer of at least 1 KB that the kernel never actually writes. */
+int ps_probe_mfma(int dtype, int iters, void *sink, double *flop, void *stream);
+
 const char *ps_strerror(int status);
 /* The HIP runtime's description of the last PS_EHIP this thread received ("" if none); static storage. */
 const char *ps_last_hip_error(void);

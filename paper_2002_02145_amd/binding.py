@@ -108,6 +108,7 @@ def _load() -> ctypes.CDLL:
         "ps_tile_kernel": (ctypes.c_int, [dp, tp]),
         "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
+        "ps_probe_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]),
         "ps_tile_rank_ws": (ctypes.c_int, [dp, ctypes.c_size_t, ctypes.c_int, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_tile_count": (ctypes.c_int, [dp]),
         "ps_tile_get": (ctypes.c_int, [dp, ctypes.c_int, tp]),
@@ -244,6 +245,13 @@ def ps_tile_select_ws(desc: ConvDesc, workspace_bytes: int) -> tuple[Tile, float
     _check(lib.ps_tile_select_ws(ctypes.byref(desc), int(workspace_bytes), ctypes.byref(t), ctypes.byref(us)),
            "ps_tile_select_ws")
     return t, us.value
+
+
+def ps_probe_mfma(dtype: int, iters: int, sink, stream=None) -> float:
+    """Launches the MFMA-only loop; returns the FLOP it performs (time it with events on the stream)."""
+    flop = ctypes.c_double()
+    _check(lib.ps_probe_mfma(int(dtype), int(iters), _ptr(sink), ctypes.byref(flop), _stream(stream)), "ps_probe_mfma")
+    return flop.value
 
 
 def ps_tile_rank_ws(desc: ConvDesc, workspace_bytes: int, k: int) -> list[tuple[Tile, float]]:

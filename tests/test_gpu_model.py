@@ -46,3 +46,17 @@ def test_run_top_k_keeps_the_fastest_of_the_models_best():
     t1, us1, rows1 = autotune.run_top_k(desc, 1, ws)
     assert t1.as_tuple() == pick.as_tuple() and len(rows1) == 1
     assert us <= 1.05 * us1          # running more candidates never loses (up to timing noise)
+
+
+def test_mfma_probe_runs_and_reports_its_flop():
+    import torch
+    from paper_2002_02145_amd import binding as ps
+    sink = torch.zeros(1024, device="cuda")
+    flop = ps.ps_probe_mfma(ps.PS_F32, 100, sink)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flop == cus * 16 * 100 * 32 * 2 * 16 * 16 * 4
+    assert ps.ps_probe_mfma(ps.PS_BF16, 100, sink) == cus * 16 * 100 * 32 * 2 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    assert not sink.any()
+    with pytest.raises(ps.PsError):
+        ps.ps_probe_mfma(7, 100, sink)
