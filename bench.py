@@ -79,6 +79,9 @@ def main(argv=None) -> int:
                     help="untimed steps first; the GPU needs tens of milliseconds of load to reach its sustained clocks")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer sweep")
+    ap.add_argument("--layer", default=None,
+                    help="time this layer of the ResNet-50-shaped sweep instead of the headline one (for profiling a "
+                         "kernel the headline does not use; the default run is the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ref-copy-mib", type=int, default=0,
                     help="also run 3 plain device-to-device copies of this many MiB (reference dispatches of known "
@@ -104,6 +107,12 @@ def main(argv=None) -> int:
 
     # ---- headline workload: ResNet-50-shaped 3x3, N=28, C=K=64, 56x56 -------------------------
     shape = wl.CFG2
+    if a.layer is not None:
+        named = {L.name: L for L in wl.resnet50_layers() + [wl.CFG3B]}
+        if a.layer not in named:
+            print(f"bench.py: unknown layer {a.layer}; one of {sorted(named)}", file=sys.stderr)
+            return 2
+        shape = named[a.layer]
     x, w = wl.relu_like(shape, 2)
     if a.dtype == "bf16":
         x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
@@ -144,7 +153,7 @@ def main(argv=None) -> int:
     kernel_ms = ev_ms
     from paper_2002_02145_amd.profile_summary import kernel_source_digest
     digest, ttile, tvariant, tbytes = MEASURED_TRAFFIC.get(a.dtype, (None, None, None, None))
-    same_launch = (digest == kernel_source_digest(a.dtype) and ttile == tile.as_tuple()
+    same_launch = (a.layer is None and digest == kernel_source_digest(a.dtype) and ttile == tile.as_tuple()
                    and tvariant == ps.ps_tile_kernel(d, tile))
     traffic = tbytes if same_launch else None
 
@@ -260,8 +269,9 @@ def main(argv=None) -> int:
         "vs_baseline": None,
         "dtype": a.dtype,
         "data": "synthetic (seeded: input U[0,1), filter N(0, sqrt(2/(C*R*S))))",
-        "config": {"workload": f"ResNet-50-shaped 3x3 conv fwd: N={shape.N} C={shape.C} K={shape.K} "
-                               f"H=W={shape.H} R=S=3 stride 1 pad 1, blocked 16c layouts, tensors resident in HBM",
+        "config": {"workload": f"ResNet-50-shaped {shape.R}x{shape.S} conv fwd ({shape.name}): N={shape.N} C={shape.C} "
+                               f"K={shape.K} H=W={shape.H} R=S={shape.R} stride {shape.stride} pad {shape.pad}, "
+                               f"blocked 16c layouts, tensors resident in HBM",
                    "tile": list(tile.as_tuple()), "tile_model_us": round(model_us, 2),
                    "timing": "warm (same buffers every step)"},
         "cold": {"us": round(cold_ms * 1e3, 2), "GFLOP/s": round(shape.flops / (cold_ms * 1e-3) * 1e-9, 1),
