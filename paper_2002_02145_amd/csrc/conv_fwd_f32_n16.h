@@ -72,8 +72,11 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     const int kb0 = tc.ktile * (Sh::KT / 16);
     const int b_begin = tc.split * a.nb_split;
 
-    // ---- loader: one instruction fills 16 pixels (lane -> pixel lane/4, 16-byte chunk lane%4), offsets per tap
+    // ---- loader: one instruction fills 16 pixels (lane -> pixel lane/4, 16-byte chunk lane%4), offsets per tap.
+    // In two stages: the taps the first D batch elements need, their loads, then the other taps under the latency of
+    // those loads (at the start of a launch every wave of the chip does this arithmetic at the same time).
     unsigned vtap[APW][TAPS];
+    int ph0[APW], pw0[APW], ppoff[APW];
 #pragma unroll
     for (int i = 0; i < APW; ++i) {
         const int grp = i * NW + wave;
@@ -82,18 +85,22 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
         fast_divmod(m, a.PQ, a.magic_pq, n, pq);
         fast_divmod(pq, a.Q, a.magic_q, p, q);
         const bool inside = (grp < Sh::PGRP) & (m < a.M);
-        const int h0 = inside ? p * a.stride - a.pad : -(1 << 24), w0 = q * a.stride - a.pad;
-        const int poff = (n * a.Cb * a.H + h0) * a.W + w0;
-#pragma unroll
-        for (int t = 0; t < TAPS; ++t) {
-            // packed: this lane fetches channels 0..3 of tap 4t + lane%4 of the sequence r*7 + s (x*37 >> 8 = x/7)
-            const int tapidx = 4 * t + (lane & 3);
-            const int r = PACKED ? (tapidx * 37) >> 8 : t / SIDE, sx = PACKED ? tapidx - 7 * r : t % SIDE;
-            const bool ok = ((unsigned)(h0 + r) < (unsigned)a.H) & ((unsigned)(w0 + sx) < (unsigned)a.W) &
-                            (!PACKED || tapidx < 49);
-            vtap[i][t] = ok ? (unsigned)((poff + r * a.W + sx) * 64 + (PACKED ? 0 : (lane & 3) * 16)) : kOobOffset;
-        }
+        ph0[i] = inside ? p * a.stride - a.pad : -(1 << 24);
+        pw0[i] = q * a.stride - a.pad;
+        ppoff[i] = (n * a.Cb * a.H + ph0[i]) * a.W + pw0[i];
     }
+#define PS_N16_TAP_OFFSETS(T0_, T1_)                                                                        \
+    _Pragma("unroll") for (int i = 0; i < APW; ++i)                                                        \
+        _Pragma("unroll") for (int t = (T0_); t < (T1_); ++t) {                                            \
+            /* packed: this lane fetches channels 0..3 of tap 4t + lane%4 of the sequence r*7 + s (x*37 >> 8 = x/7) */ \
+            const int tapidx = 4 * t + (lane & 3);                                                         \
+            const int r = PACKED ? (tapidx * 37) >> 8 : t / SIDE, sx = PACKED ? tapidx - 7 * r : t % SIDE; \
+            const bool ok = ((unsigned)(ph0[i] + r) < (unsigned)a.H) & ((unsigned)(pw0[i] + sx) < (unsigned)a.W) & \
+                            (!PACKED || tapidx < 49);                                                      \
+            vtap[i][t] = ok ? (unsigned)((ppoff[i] + r * a.W + sx) * 64 + (PACKED ? 0 : (lane & 3) * 16)) : kOobOffset; \
+        }
+    constexpr int FIRST_TAPS = D < TAPS ? D : TAPS;
+    PS_N16_TAP_OFFSETS(0, FIRST_TAPS)
     int wsoff[WPW];
     bool wok[WPW];
     wok[0] = kb0 + wave < a.Kb;  // wave w fetches filter block kb0 + w, the one it multiplies with
@@ -106,6 +113,21 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     // [1] is for the last element, where only tap 48 exists
     const unsigned wpk = (lane >> 4) == 3 ? kOobOffset : (unsigned)(((lane >> 2) & 3) * 1024 + (lane >> 4) * 64 + (lane & 3) * 16);
     const unsigned vw[2] = {PACKED ? wpk : wsrc, PACKED ? (((lane >> 2) & 3) == 0 ? wpk : kOobOffset) : wsrc};
+
+    const int nb = a.nb_split;
+    int cb0 = b_begin / TAPS;
+#pragma unroll
+    for (int e = 0; e < D; ++e)
+        issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, PACKED>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+    __builtin_amdgcn_sched_barrier(0);  // the loads above stay in front of the arithmetic below
+    PS_N16_TAP_OFFSETS(FIRST_TAPS, TAPS)
+#undef PS_N16_TAP_OFFSETS
+    // (an empty statement that "uses" every offset: otherwise the compiler sinks this arithmetic to its first use,
+    // behind the wait for the first loads)
+#pragma unroll
+    for (int i = 0; i < APW; ++i)
+#pragma unroll
+        for (int t = FIRST_TAPS; t < TAPS; ++t) asm volatile("" ::"v"(vtap[i][t]));
 
     // ---- reader -------------------------------------------------------------------------------------
     const int paddr = l16 * 64 + g * 16;                                  // + tile * 1024
@@ -126,11 +148,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     }
 
     // ---- pipeline (as the 32x32 kernels: ring of NBUF batch elements, unrolled over lcm(NBUF, taps)) --------
-    const int nb = a.nb_split;
-    int cb0 = b_begin / TAPS;
-#pragma unroll
-    for (int e = 0; e < D; ++e)
-        issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, PACKED>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+    __builtin_amdgcn_sched_barrier(0);  // ... and all of it in front of the wait for them
     wait_vm_and_barrier<(D - 1) * LPE>();
     PS_N16_READ(0, 0)
     for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
