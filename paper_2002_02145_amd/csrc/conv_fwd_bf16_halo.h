@@ -119,6 +119,12 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_halo_kernel(const 
         vw[i] = ok ? (unsigned)((kb0 + kb) * a.NB * 512 + within * 16) : kOobOffset;  // the c-block goes into the scalar offset
     }
 
+    // The first two c-blocks are requested now; the reader's addresses and the cleared accumulators are computed
+    // under their latency (all workgroups of a launch start at once, so nothing else would hide that arithmetic).
+    issue_halo_cblock<Sh>(a, lds, vh, vw, wave, 0, cb_begin, 0 < ncb);
+    issue_halo_cblock<Sh>(a, lds, vh, vw, wave, 1, cb_begin + 1, 1 < ncb);
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- reader: patch address of every tap for this lane's pixels, filter rows ---------------------------
     int paddr[TM][9], waddr[TK];
 #pragma unroll
@@ -156,8 +162,13 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_halo_kernel(const 
     }
 
     // ---- pipeline: one c-block per ring slot, two slots, the next c-block in flight while this one computes
-    issue_halo_cblock<Sh>(a, lds, vh, vw, wave, 0, cb_begin, 0 < ncb);
-    issue_halo_cblock<Sh>(a, lds, vh, vw, wave, 1, cb_begin + 1, 1 < ncb);
+    // (every address the loop needs exists before the wait: the compiler would otherwise sink that arithmetic to its
+    // first use, behind the arrival of the first c-block)
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) asm volatile("" ::"v"(paddr[tm][t]));
+    __builtin_amdgcn_sched_barrier(0);
     wait_vm_and_barrier<LPC>();
     PS_HALO_READ(0, 0, 0)
     for (int c0 = 0; c0 < ncb; c0 += 2) {
