@@ -204,6 +204,9 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kloop_kernel(const ConvA
         }
         // the slice after next goes into the buffer just read (all its reads have been consumed by the MFMAs above)
         if (J + 2 < kKloopTiles) kloop_load_slice<MT, CB, FUSED>(a, wbase + buf * Sh::W_SLICE, kb0 + (J + 2) * 4, wsrc);
+        // The wait counts above rely on this order: every load of the slice in front of every store of the tile.
+        // Without the fence the instruction scheduler interleaves the two groups.
+        __builtin_amdgcn_sched_barrier(0);
         {
             const int kb = kb0 + J * 4;
             const __amdgpu_buffer_rsrc_t rout = make_rsrc(a.out, kb < a.Kb ? out_bytes : 0u);  // nothing beyond K
@@ -231,6 +234,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kloop_kernel(const ConvA
             }
             // the next tile's first MFMAs overwrite the accumulators just stored: same guard
             asm volatile("s_nop 1" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);  // ... and the stores in front of whatever memory operation comes next
         }
     }
 #undef PS_KLOOP_READ

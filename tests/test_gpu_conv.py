@@ -146,3 +146,41 @@ def test_tensors_near_the_size_limit(shape):
     with pytest.raises(ps.PsError) as e:
         ps.ps_out_dims(ps.ConvDesc.of(too_big))
     assert e.value.status == ps.PS_EUNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype", [0, 1], ids=["fp32", "bf16"])
+def test_every_candidate_tile_at_full_size(dtype):
+    """Every tile the enumerator offers for every layer of the sweep, at N = 28: the oracle checks the first image of
+    the model's pick (the sweep test above checks all of it), and every other candidate must agree with the pick on
+    every output element up to the reordering of fp32 additions (compared on the device in blocked order; the data
+    are the library's outputs on both sides, so no reference arithmetic is involved).  Covers the kernels the model
+    does not pick (32x32- against 16x16-tile, gathering against patch loop, split reductions) at their real grids."""
+    import torch
+    from gpu_util import DEV, all_tiles, blocked_inputs
+    from paper_2002_02145_amd import binding as ps
+    for i, shape in enumerate(wl.resnet50_layers()):
+        x, w = _prep(shape, wl.relu_like, wl.sweep_seed(i), dtype)
+        d, xb, wb = blocked_inputs(shape, x, w, dtype)
+        n_out = ps.ps_blocked_out_bytes(d) // 4
+        ws = torch.empty((256 << 20) // 4, dtype=torch.float32, device=DEV)
+        ref = torch.full((n_out,), float("nan"), dtype=torch.float32, device=DEV)
+        ps.ps_conv2d_fwd_ws(d, None, xb, wb, ref, ws, ws.numel() * 4)
+        P, Q = ps.ps_out_dims(d)
+        first = ref.view(shape.N, shape.K // 16, P, Q, 16)[0].permute(0, 3, 1, 2).reshape(shape.K, P, Q).cpu().numpy()
+        out, mag = oracle.conv2d_fwd(shape, x, w, images=(0, 1))
+        assert oracle.normalised_error(first[None], out[:1], mag[:1]) <= TOL[dtype], shape.name
+        scale = float(ref.abs().max())
+        # the K-dimension of a sum is at most 4608 terms: reordering moves a result by a few units in the last place
+        # of its largest partial sum; 1e-5 (fp32) of the layer's largest output is far above that and far below any
+        # misplaced or missing term
+        bound = (1e-5 if dtype == 0 else 1e-5) * scale
+        got = torch.empty_like(ref)
+        for t in all_tiles(shape, dtype):
+            need = ps.ps_workspace_bytes(d, t)
+            if need > ws.numel() * 4:
+                continue
+            got.fill_(float("nan"))
+            ps.ps_conv2d_fwd_ws(d, t, xb, wb, got, ws if need else None, need)
+            diff = float((got - ref).abs().max())            # NaN if anything was left unwritten
+            assert diff <= bound, f"{shape.name} dtype={dtype} {t}: max |diff| {diff} against {bound}"
+        del ws, ref, got, xb, wb
