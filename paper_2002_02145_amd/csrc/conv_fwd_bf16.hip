@@ -235,8 +235,10 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
         constexpr int U = NBUF / ct_gcd(NBUF, TG) * TG;  // iterations per unrolled block; U * G is a multiple of TAPS
         int cb0 = b_begin / TAPS;
 #pragma unroll
-        for (int e = 0; e < D; ++e)
+        for (int e = 0; e < D; ++e) {
             issue_baked_bf16<Sh, NBUF, G, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+            __builtin_amdgcn_sched_barrier(0);  // the wait counts assume the elements' loads stay in this order
+        }
         wait_vm_and_barrier<(D - 1) * LPS>();
         read_frags(0, 0);
         for (int s0 = 0; s0 < nslot; s0 += U, cb0 += U * G / TAPS) {
@@ -258,7 +260,10 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < D; ++e) issue_loads(e);
+        for (int e = 0; e < D; ++e) {
+            issue_loads(e);
+            __builtin_amdgcn_sched_barrier(0);  // the wait counts assume the elements' loads stay in this order
+        }
         wait_vm_and_barrier<(D - 1) * LPS>();
         read_frags(0, 0);
         for (int s0 = 0; s0 < nslot; s0 += NBUF) {

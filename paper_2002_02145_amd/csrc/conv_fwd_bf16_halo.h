@@ -122,6 +122,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_halo_kernel(const 
     // The first two c-blocks are requested now; the reader's addresses and the cleared accumulators are computed
     // under their latency (all workgroups of a launch start at once, so nothing else would hide that arithmetic).
     issue_halo_cblock<Sh>(a, lds, vh, vw, wave, 0, cb_begin, 0 < ncb);
+    __builtin_amdgcn_sched_barrier(0);  // the wait counts assume the elements' loads stay in this order
     issue_halo_cblock<Sh>(a, lds, vh, vw, wave, 1, cb_begin + 1, 1 < ncb);
     __builtin_amdgcn_sched_barrier(0);
 

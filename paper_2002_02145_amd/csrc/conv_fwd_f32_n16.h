@@ -117,8 +117,10 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     const int nb = a.nb_split;
     int cb0 = b_begin / TAPS;
 #pragma unroll
-    for (int e = 0; e < D; ++e)
+    for (int e = 0; e < D; ++e) {
         issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, PACKED>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+        __builtin_amdgcn_sched_barrier(0);  // the wait counts assume the elements' loads stay in this order
+    }
     __builtin_amdgcn_sched_barrier(0);  // the loads above stay in front of the arithmetic below
     PS_N16_TAP_OFFSETS(FIRST_TAPS, TAPS)
 #undef PS_N16_TAP_OFFSETS

@@ -109,6 +109,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kloop_kernel(const ConvA
     const unsigned wsrc = (unsigned)((4 * ((lane >> 2) & 3) + (lane >> 4)) * 64 + (lane & 3) * 16);
     char *const wbase = lds + Sh::P_BYTES + wave * 2 * Sh::W_SLICE;
     kloop_load_first<MT, CB, FUSED>(a, lds, wbase, wave, kb0, vpix, wsrc);
+    __builtin_amdgcn_sched_barrier(0);  // slice 1 after everything the first wait is for
     kloop_load_slice<MT, CB, FUSED>(a, wbase + Sh::W_SLICE, kb0 + 4, wsrc);
 
     // ---- output offsets, once for all tiles (as in conv_fwd_f32_n16.h: scalar running position, lanes only

@@ -527,8 +527,10 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         constexpr int U = NBUF / ct_gcd(NBUF, TAPS) * TAPS;
         int cb0 = b_begin / TAPS;
 #pragma unroll
-        for (int e = 0; e < D; ++e)
+        for (int e = 0; e < D; ++e) {
             issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4, SIDE>(a, lds, vtap, wsoff, wok, vw, wave, e, e, 0, cb0);
+            __builtin_amdgcn_sched_barrier(0);  // the wait counts assume the elements' loads stay in this order
+        }
         wait_vm_and_barrier<(D - 1) * LPE>();
         read_frags(0, 0);
         for (int b0 = 0; b0 < nb; b0 += U, cb0 += U / TAPS) {
@@ -553,7 +555,10 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < D; ++e) issue_loads(e);  // elements 0..D-1 (zero-filled beyond the range)
+        for (int e = 0; e < D; ++e) {  // elements 0..D-1 (zero-filled beyond the range)
+            issue_loads(e);
+            __builtin_amdgcn_sched_barrier(0);  // the wait counts assume the elements' loads stay in this order
+        }
         wait_vm_and_barrier<(D - 1) * LPE>();        // element 0 has landed everywhere
         read_frags(0, 0);
         // iteration b: slot b % NBUF, fragment parity b % 2; unrolled by NBUF (even) so both are static.
