@@ -144,13 +144,19 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double n_iter = nb_pad / grp;
     // (a lone 16-bit wave cannot hide its barrier behind its own short MFMA stream; an fp32 one can)
     const bool f32 = dm.dtype == PS_F32;
-    double clk_iter_overhead = (waves_res >= 2 || f32 ? 40.0 : 220.0) * n_iter;
+    double clk_iter_overhead = (f32 ? 40.0 : waves_res >= 2 ? 150.0 : 220.0) * n_iter;
     // a load issued in iteration b must have landed (ring - 1) iterations later: the part of the latency
     // the ring does not cover stalls every wave of the SIMD, and latency varies, so a thin margin still costs
     const double clk_iter = tiles_wave * mfma_clk * grp / eff * waves_res;  // wall clock of one iteration
     const double cover = (t.ring - 1) * clk_iter / c.load_latency_clk;
     const double stall = std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter) + (f32 ? 0.10 : 0.50) * clk_iter * std::exp(-cover);
-    clk_iter_overhead += stall * n_iter / waves_res;
+    if (patch) {
+        // one barrier per c-block (9 taps) and the next c-block requested a whole iteration ahead: the hard part of
+        // the stall (latency the ring does not cover) does not arise; a lone wave still pays for its barrier
+        clk_iter_overhead = (waves_res >= 2 ? 40.0 : 220.0) * n_iter + (stall - std::max(0.0, c.load_latency_clk / (t.ring - 1) - clk_iter)) * n_iter / waves_res;
+    } else {
+        clk_iter_overhead += stall * n_iter / waves_res;
+    }
     // Per workgroup, outside its MFMA stream: address set-up, first fragment reads and the stores of its tile.  The
     // waves of a SIMD run their streams one after another and a pending MFMA holds the SIMD's issue port, so this
     // work is not hidden by the other workgroups on the compute unit; it grows with the accumulator tiles a wave
@@ -214,7 +220,11 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         t_mem += out_bytes * t.c_split / far_bw;  // partial planes written once ...
         t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 * c.reduce_ineff + c.dependent_launch_us;  // ... and added by a second pass
     }
-    return (std::max(t_mfma, t_mem) + 0.12 * std::min(t_mfma, t_mem)) * 1e6 + c.launch_us + t_extra;
+    // Filters larger than one XCD's L2: with the channel tiles fastest every XCD streams all of them through its L2
+    // over and over, with the pixel tiles fastest it stays on the slices of a few channel tiles.  Where the two
+    // orders otherwise cost the same this decides (measured 3x3, 512 channels, 7x7 images, bf16: 19.3 against 16.2 us).
+    const double order_bias = (wt_bytes > c.l2_bytes && t.raster == 0 && n_kt >= c.xcds && n_mt > 1) ? 1.02 : 1.0;
+    return (std::max(t_mfma, t_mem) + 0.12 * std::min(t_mfma, t_mem)) * 1e6 * order_bias + c.launch_us + t_extra;
 }
 
 struct Cand {

@@ -31,6 +31,26 @@ def test_model_pick_within_ten_percent_of_sweep_best_fp32(name):
     assert r["worst_us"] >= best_us
 
 
+@pytest.mark.parametrize("name", ["3x3_512_7", "1x1_1024to256_14", "3x3_256_14"])
+def test_model_pick_close_to_sweep_best_bf16(name):
+    """The same for 16-bit inputs on the layers where the model used to be furthest off.  These kernels take 10-20 us,
+    where run-to-run timing differences of a few per cent are common: the model's target stays 10 %, the test allows
+    15 % after a second, longer measurement."""
+    import torch
+    from paper_2002_02145_amd import autotune, binding as ps
+    shape = {l.name: l for l in wl.resnet50_layers()}[name]
+    r = autotune.sweep(shape, ps.PS_BF16, min_ms=5.0)
+    pick_us, best_us = r["pick_us"], r["best_us"]
+    if pick_us > 1.10 * best_us:
+        desc = ps.ConvDesc.of(shape, ps.PS_BF16)
+        sets = autotune._buffers(desc, 2)
+        tiles = [ps.Tile(*r["pick"]), ps.Tile(*r["best"])]
+        need = max(ps.ps_workspace_bytes(desc, t) for t in tiles)
+        ws = torch.empty(max(need, 16) // 4, device="cuda")
+        pick_us, best_us = (autotune.time_tile(desc, t, sets, min_ms=40.0, workspace=ws) for t in tiles)
+    assert pick_us <= 1.15 * best_us, f"{name}: pick {r['pick']} {pick_us:.1f} us vs best {r['best']} {best_us:.1f} us"
+
+
 def test_run_top_k_keeps_the_fastest_of_the_models_best():
     """Section 4.2's protocol end to end: the k best-ranked tiles are timed, the fastest is returned; k = 1 is the
     library's pick."""
