@@ -131,3 +131,37 @@ def test_fused_rejects_bad_arguments():
         ps.ps_conv2d_fwd_fused(d, None, xb, wb, ob, None, 0, out_dtype=5)
     assert e.value.status == ps.PS_EUNSUPPORTED
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", [ps.PS_F32, ps.PS_BF16], ids=["fp32", "bf16"])
+def test_fused_every_candidate_tile_at_full_size(dtype):
+    """Every tile of every layer of the sweep at N = 28 with bias and max(., 0), fp32 and bf16 output, against the same
+    two elementwise steps applied (torch, on the device) to the unfused output of the model's pick, which
+    tests/test_gpu_conv.py checks against the oracle.  The fused kernels are separate instances with their own
+    instruction schedules; this runs each of them at its real grid."""
+    for i, shape in enumerate(wl.resnet50_layers()):
+        x, w = wl.relu_like(shape, 200 + i)
+        if dtype == ps.PS_BF16:
+            x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
+        d, xb, wb = blocked_inputs(shape, x, w, dtype)
+        P, Q = ps.ps_out_dims(d)
+        n_out = shape.N * shape.K * P * Q
+        ws = torch.empty((256 << 20) // 4, dtype=torch.float32, device=DEV)
+        ref = torch.empty(n_out, dtype=torch.float32, device=DEV)
+        ps.ps_conv2d_fwd_ws(d, None, xb, wb, ref, ws, ws.numel() * 4)
+        bias = torch.from_numpy(np.random.default_rng(i).standard_normal(shape.K).astype(np.float32)).to(DEV)
+        want = torch.clamp(ref.view(shape.N, shape.K // 16, P, Q, 16) + bias.view(1, shape.K // 16, 1, 1, 16), min=0).reshape(-1)
+        scale = float(want.abs().max())
+        for out_dtype, odt in ((ps.PS_F32, torch.float32), (ps.PS_BF16, torch.bfloat16)):
+            # reordered fp32 additions, plus one bf16 rounding (2^-8 relative) of the stored value
+            bound = 1e-5 * scale + (scale * 2.0 ** -8 if out_dtype == ps.PS_BF16 else 0.0)
+            got = torch.empty(n_out, dtype=odt, device=DEV)
+            for t in all_tiles(shape, dtype):
+                need = ps.ps_workspace_bytes(d, t)
+                if need > ws.numel() * 4:
+                    continue
+                got.fill_(float("nan"))
+                ps.ps_conv2d_fwd_fused(d, t, xb, wb, got, ws if need else None, need, bias=bias, relu=True, out_dtype=out_dtype)
+                diff = float((got.float() - want).abs().max())
+                assert diff <= bound, f"{shape.name} dtype={dtype} out={out_dtype} {t}: {diff} against {bound}"
+        del ws, ref, got, xb, wb, want
