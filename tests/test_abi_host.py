@@ -108,3 +108,30 @@ def test_tile_enumerator_and_model(ps):
             ps.ps_tile_get(d, n)
     assert not ps.ps_tile_valid(ps.ConvDesc.of(wl.CFG1), ps.Tile(128, 128, 2, 1, 0))   # K = 64 < kt
     assert ps.ps_tile_cost_us(ps.ConvDesc.of(wl.CFG1), ps.Tile(128, 128, 2, 1, 0)) < 0
+
+
+def test_specialised_shapes_are_refused_where_they_do_not_apply(ps):
+    """The 16x16-tile kernels have no loop for a runtime filter size and no atomic epilogue, the pixel-stationary ones
+    only serve 1x1 filters over exactly 64 channels: the validity call is what keeps them from being launched on
+    anything else."""
+    def valid(shape, tile, dtype=None):
+        return ps.ps_tile_valid(ps.ConvDesc.of(shape, ps.PS_F32 if dtype is None else dtype), ps.Tile(*tile))
+    S = wl.ConvShape
+    stationary, n16 = (256, 176, 2, 1, 0), (64, 176, 2, 1, 0)
+    assert valid(S(2, 64, 8, 8, 256, 1, 1, 1, 0), stationary)
+    assert not valid(S(2, 128, 8, 8, 256, 1, 1, 1, 0), stationary)          # 8 c-blocks
+    assert not valid(S(2, 48, 8, 8, 256, 1, 1, 1, 0), stationary)           # 3 c-blocks
+    assert not valid(S(2, 64, 8, 8, 256, 3, 3, 1, 1), stationary)           # not 1x1
+    assert not valid(S(2, 64, 3, 3, 256, 1, 1, 1, 0), stationary)           # images of fewer than 16 pixels
+    assert not valid(S(2, 64, 8, 8, 256, 1, 1, 1, 0), (256, 176, 2, 2, 0))  # no split reduction
+    assert not valid(S(2, 64, 8, 8, 256, 1, 1, 1, 0), stationary, ps.PS_BF16)
+    assert valid(S(2, 64, 8, 8, 64, 3, 3, 1, 1), n16) and valid(S(2, 64, 8, 8, 64, 1, 1, 2, 0), n16)
+    assert not valid(S(2, 64, 8, 8, 64, 5, 5, 1, 2), n16)                   # no baked 5x5 loop
+    assert not valid(S(2, 64, 8, 8, 64, 3, 3, 1, 1), (64, 176, 2, 2, 0))    # no atomic epilogue
+    assert valid(S(2, 3, 20, 20, 64, 7, 7, 2, 3), n16)                      # tap-packed stem, 3 channels
+    assert not valid(S(2, 4, 20, 20, 64, 7, 7, 2, 3), n16)                  # 4 channels: only the 32x32 kernels
+    assert valid(S(2, 4, 20, 20, 64, 7, 7, 2, 3), (64, 128, 2, 1, 0))
+    # and the variant report names them
+    d = ps.ConvDesc.of(S(2, 64, 8, 8, 256, 1, 1, 1, 0))
+    assert ps.KERNEL_NAMES[ps.ps_tile_kernel(d, ps.Tile(*stationary))] == "1x1 pixel-stationary"
+    assert ps.KERNEL_NAMES[ps.ps_tile_kernel(ps.ConvDesc.of(S(2, 3, 20, 20, 64, 7, 7, 2, 3)), ps.Tile(*n16))] == "7x7 tap-packed"
