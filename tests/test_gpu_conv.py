@@ -158,7 +158,7 @@ def test_every_candidate_tile_at_full_size(dtype):
     import torch
     from gpu_util import DEV, all_tiles, blocked_inputs
     from paper_2002_02145_amd import binding as ps
-    for i, shape in enumerate(wl.resnet50_layers()):
+    for i, shape in enumerate(wl.resnet50_layers() + [wl.CFG3B]):
         x, w = _prep(shape, wl.relu_like, wl.sweep_seed(i), dtype)
         d, xb, wb = blocked_inputs(shape, x, w, dtype)
         n_out = ps.ps_blocked_out_bytes(d) // 4

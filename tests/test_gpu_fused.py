@@ -139,7 +139,7 @@ def test_fused_every_candidate_tile_at_full_size(dtype):
     two elementwise steps applied (torch, on the device) to the unfused output of the model's pick, which
     tests/test_gpu_conv.py checks against the oracle.  The fused kernels are separate instances with their own
     instruction schedules; this runs each of them at its real grid."""
-    for i, shape in enumerate(wl.resnet50_layers()):
+    for i, shape in enumerate(wl.resnet50_layers() + [wl.CFG3B]):
         x, w = wl.relu_like(shape, 200 + i)
         if dtype == ps.PS_BF16:
             x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
