@@ -1,8 +1,8 @@
-// fp32 1x1 convolution with a short reduction (C = 64 or 128) on 16x16x4 MFMA tiles, pixels stationary:
+// fp32 1x1 convolution with a short reduction (C = 64: 4 c-blocks) on 16x16x4 MFMA tiles, pixels stationary:
 // a workgroup loads its MT pixels with ALL their input channels into LDS once and then walks over 4 consecutive
 // 64-channel output tiles (256 output channels), streaming only filter slices.
 //
-// Why: with 4 or 8 batch elements per tile the kernels of conv_fwd_f32_n16.h spend as long starting and ending a
+// Why: with 4 batch elements per tile the kernels of conv_fwd_f32_n16.h spend as long starting and ending a
 // workgroup (index arithmetic, first loads, store drain until the slot is refilled) as in MFMAs; measured on
 // 64 -> 256 channels at 56x56: every tile shape lands at 57 % of the matrix-core peak.  Here the prologue runs once
 // per 4 output tiles, the pixels are fetched once instead of 4 times, and a wave never waits for its stores:
@@ -243,7 +243,8 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kloop_kernel(const ConvA
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-// c-blocks 4 and 8 are compiled (C = 64 and 128); the host offers these shapes to nothing else
+// compiled for 4 c-blocks (C = 64); the host offers these shapes to nothing else (with C = 128 the pixels and the
+// double-buffered slices leave room for one workgroup per compute unit only, which gains nothing)
 template <int MT>
 void launch_f32_n16_kloop(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
