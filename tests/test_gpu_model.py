@@ -65,7 +65,7 @@ def test_run_top_k_keeps_the_fastest_of_the_models_best():
     assert us == min(r[2] for r in rows) and tile.as_tuple() in {r[0].as_tuple() for r in rows}
     t1, us1, rows1 = autotune.run_top_k(desc, 1, ws)
     assert t1.as_tuple() == pick.as_tuple() and len(rows1) == 1
-    assert us <= 1.05 * us1          # running more candidates never loses (up to timing noise)
+    assert us <= 1.10 * us1          # running more candidates never loses (up to timing noise)
 
 
 def test_mfma_probe_runs_and_reports_its_flop():
