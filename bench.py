@@ -88,8 +88,8 @@ def main(argv=None) -> int:
                          "size for scaling FETCH_SIZE / WRITE_SIZE counter runs)")
     a = ap.parse_args(argv)
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (convolution forward needs no exchange between "
-              "GPUs; see DESIGN.md for how it would shard); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this library runs on one GPU only (forward convolution shards over images with no exchange "
+              "between GPUs, so several GPUs are several independent runs); rerun with --gpus 1", file=sys.stderr)
         return 2
 
     import torch
