@@ -1,6 +1,6 @@
 """GPU forward convolution (through the C ABI) against the CPU oracle, element by element.
 
-Tolerances (stated by the task's accuracy target): max |gpu - oracle| / sum|x*w| <= 1e-4 for fp32
+Tolerances: max |gpu - oracle| / sum|x*w| <= 1e-4 for fp32
 inputs and <= 2e-2 for bf16 inputs with fp32 accumulation; outputs whose magnitude sum is zero must
 be exactly zero; integer-valued inputs must reproduce the exact result."""
 import numpy as np
