@@ -49,8 +49,8 @@ struct Chip {
     double load_latency_clk = 1150.0;         // global load to LDS, L2 hit under load
     double fill_clk = 4500.0;                 // first loads of a workgroup (nothing to overlap with)
     double launch_us = 1.5;
-    double dependent_launch_us = 3.5;         // a kernel that has to wait for the previous one to drain
-    double reduce_ineff = 1.4;                // the plane-adding pass against streaming bandwidth
+    double dependent_launch_us = 5.0;         // a kernel that has to wait for the previous one to drain
+    double reduce_ineff = 2.0;                // the plane-adding pass against streaming bandwidth
 };
 
 const Chip kChip;
@@ -162,8 +162,8 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     // work is not hidden by the other workgroups on the compute unit; it grows with the accumulator tiles a wave
     // has to store (atomics cost more per tile), and in the 16x16-tile kernels with the pixel tiles every wave
     // walks over.  The first loads of a launch have nothing to overlap with at all (fill_clk, once).
-    const double clk_wg = (tiles_wave * (t.c_split > 1 && !with_ws ? 1900.0 : 1250.0) +
-                           (sh.baked_only ? 200.0 * (t.mt / 16.0) : 0.0)) * waves_wg / 4.0;  // per SIMD
+    const double clk_tile = t.c_split > 1 && !with_ws ? 1900.0 : (sh.baked_only ? 900.0 : 1250.0);
+    const double clk_wg = (tiles_wave * clk_tile + (sh.baked_only ? 200.0 * (t.mt / 16.0) : 0.0)) * waves_wg / 4.0;  // per SIMD
     double t_mfma;
     if (sh.stationary) {
         // One workgroup walks over kt / 64 output tiles with its pixels resident: set-up and the first loads (all
@@ -173,7 +173,9 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         const double clk_boundary = tiles * (150.0 + 90.0 * t.mt / 16.0);
         t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + 7700.0 + per_cu * clk_boundary) / c.clock_hz;
     } else if (f32) {
-        t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + c.fill_clk + per_cu * clk_wg +
+        // Workgroups that share a compute unit hide part of each other's set-up and stores.
+        const double hidden = 1.0 + 0.5 * (std::min(occ, per_cu) - 1.0);
+        t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + c.fill_clk + per_cu * clk_wg / hidden +
                   per_cu * (t.ring - 2) * 250.0) / c.clock_hz;  // a deeper ring takes longer to fill, per workgroup
     } else {
         // 16-bit tiles are short enough that their set-up and stores mostly hide behind other workgroups; what
