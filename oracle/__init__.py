@@ -4,7 +4,9 @@ Holds the plain, slow, double-precision statement of what the GPU path computes:
 
 * ``conv2d_fwd`` / ``conv2d_fwd_point`` -- forward convolution by its definition
   (C code in ``conv_oracle.c``; the paper's Fig. 4 with the channel blocking undone);
-* ``layout`` -- the blocked tensor layouts of Fig. 4 written as index identities in numpy.
+* ``layout`` -- the blocked tensor layouts of Fig. 4 written as index identities in numpy;
+* ``reuse_oracle`` -- Section 4's working-set analysis and cost function by brute-force enumeration;
+* ``ranker_oracle`` -- Section 4.2.2's pairwise network and tournament in float64 numpy.
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this package.
 It imports nothing from the GPU package and shares no code with it.
