@@ -123,6 +123,12 @@ def _load() -> ctypes.CDLL:
                                            ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
         "ps_reuse_cost": (ctypes.c_double, [ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_int64,
                                             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
+        "ps_tile_reuse_levels": (ctypes.c_int, [dp, tp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
+        "ps_tile_level_times_ws": (ctypes.c_int, [dp, tp, ctypes.POINTER(ctypes.c_double)]),
+        "ps_tile_rank_dnn_scratch_bytes": (ctypes.c_size_t, [dp]),
+        "ps_tile_rank_dnn": (ctypes.c_int, [dp, ctypes.c_size_t, ctypes.c_int, vp, ctypes.c_float, vp, ctypes.c_size_t,
+                                            ctypes.c_int, tp, i32p, vp]),
+        "ps_ranker_play": (ctypes.c_int, [vp, ctypes.c_int, vp, ctypes.c_float, vp, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -327,3 +333,52 @@ def ps_reuse_cost(level_ws, mem_ws: int, lat, bw) -> float:
     if c < 0:
         raise PsError(PS_EINVAL, "ps_reuse_cost")
     return c
+
+
+PS_RANKER_STATS = 4
+PS_RANKER_LEVELS = 3
+PS_RANKER_PARAMS = 3338
+PS_RANKER_MAX_VARIANTS = 8192
+PS_RANKER_WORKING_SETS, PS_RANKER_LEVEL_TIMES = 0, 1
+
+
+def ps_tile_reuse_levels(desc: ConvDesc, tile: Tile) -> tuple[list[int], int]:
+    """Working-set sizes (bytes) of a candidate tile at registers+LDS, L2 and Infinity Cache, and what is left to
+    memory (Algorithms 1 and 2 on the tile's workgroup-level loop nest)."""
+    lvl = (ctypes.c_int64 * PS_RANKER_LEVELS)()
+    mem = ctypes.c_int64()
+    _check(lib.ps_tile_reuse_levels(ctypes.byref(desc), ctypes.byref(tile), lvl, ctypes.byref(mem)),
+           "ps_tile_reuse_levels")
+    return [lvl[i] for i in range(PS_RANKER_LEVELS)], mem.value
+
+
+def ps_tile_level_times_ws(desc: ConvDesc, tile: Tile) -> list[float]:
+    """The four parts of the tile model's cost (us): matrix cores, traffic into the compute units, traffic beyond
+    L2, launches and extra passes."""
+    out = (ctypes.c_double * PS_RANKER_STATS)()
+    _check(lib.ps_tile_level_times_ws(ctypes.byref(desc), ctypes.byref(tile), out), "ps_tile_level_times_ws")
+    return [out[i] for i in range(PS_RANKER_STATS)]
+
+
+def ps_ranker_play(stats, n: int, params, theta: float, wins, probs=None, stream=None) -> None:
+    """The tournament of Section 4.2.2: stats float32 [n][4], params float32 [PS_RANKER_PARAMS], wins int32 [n],
+    probs float32 [n][n][2] or None -- all device tensors."""
+    _check(lib.ps_ranker_play(_ptr(stats), n, _ptr(params), theta, _ptr(wins), None if probs is None else _ptr(probs),
+                              _stream(stream)), "ps_ranker_play")
+
+
+def ps_tile_rank_dnn_scratch_bytes(desc: ConvDesc) -> int:
+    return int(lib.ps_tile_rank_dnn_scratch_bytes(ctypes.byref(desc)))
+
+
+def ps_tile_rank_dnn(desc: ConvDesc, workspace_bytes: int, stats_kind: int, params, theta: float, scratch,
+                     scratch_bytes: int, k: int, stream=None) -> list[tuple[Tile, int]]:
+    """The k candidates with the most tournament wins, [(tile, wins), ...]; params and scratch are device tensors.
+    Waits for the stream."""
+    tiles = (Tile * k)()
+    wins = (ctypes.c_int32 * k)()
+    n = lib.ps_tile_rank_dnn(ctypes.byref(desc), workspace_bytes, stats_kind, _ptr(params), theta, _ptr(scratch),
+                             scratch_bytes, k, tiles, wins, _stream(stream))
+    if n < 0:
+        raise PsError(n, "ps_tile_rank_dnn")
+    return [(Tile(*tiles[i].as_tuple()), int(wins[i])) for i in range(n)]

@@ -105,7 +105,9 @@ int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
 // one XCD -> that XCD's L2 if they fit, else the Infinity Cache, else HBM.  The cost is the time the
 // slowest level needs for the bytes it has to move (Eq. 1 with latency folded into per-workgroup
 // fill and launch terms), plus a fraction of the second-slowest for imperfect overlap.
-double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool with_ws)
+// terms, if given, receives the parts the total is made of (us): matrix cores with their per-workgroup overheads,
+// traffic into the compute units, traffic beyond L2, and launches plus extra passes.
+double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool with_ws, double *terms = nullptr)
 {
     const Chip &c = kChip;
     const double M = (double)dm.M;
@@ -213,7 +215,8 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         beyond_l2 += refetch * std::min(1.0, (xcd_ws - c.l2_bytes) / xcd_ws);
     }
     const double far_bw = total <= 0.7 * c.mall_bytes ? c.mall_bw : c.hbm_bw;
-    double t_mem = std::max(cu_bytes / c.l2_bw, beyond_l2 / far_bw);
+    const double t_near = cu_bytes / c.l2_bw, t_far = beyond_l2 / far_bw;
+    double t_mem = std::max(t_near, t_far);
     double t_extra = 0.0;
     if (t.c_split > 1 && !with_ws) {
         t_mem += out_bytes * t.c_split / c.atomic_bw;   // atomic accumulation of partial tiles
@@ -226,6 +229,12 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     // over and over, with the pixel tiles fastest it stays on the slices of a few channel tiles.  Where the two
     // orders otherwise cost the same this decides (measured 3x3, 512 channels, 7x7 images, bf16: 19.3 against 16.2 us).
     const double order_bias = (wt_bytes > c.l2_bytes && t.raster == 0 && n_kt >= c.xcds && n_mt > 1) ? 1.02 : 1.0;
+    if (terms) {
+        terms[0] = t_mfma * 1e6;
+        terms[1] = t_near * 1e6;
+        terms[2] = (t_far + (t_mem - std::max(t_near, t_far))) * 1e6;  // with the partial tiles of a split reduction
+        terms[3] = c.launch_us + t_extra;
+    }
     return (std::max(t_mfma, t_mem) + 0.12 * std::min(t_mfma, t_mem)) * 1e6 * order_bias + c.launch_us + t_extra;
 }
 
@@ -313,6 +322,23 @@ static double cost_of(const ps_conv_desc *d, const ps_tile *t, bool with_ws)
         if (shapes[i].kt == t->kt && shapes[i].mt == t->mt && shapes[i].ring == t->ring)
             return model_cost(dm, *t, shapes[i], with_ws);
     return -1.0;
+}
+
+extern "C" int ps_tile_level_times_ws(const ps_conv_desc *d, const ps_tile *t, double times_us[4])
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!t || !times_us) return PS_EINVAL;
+    if ((rc = ps_tile_valid(d, t)) != PS_OK) return rc;
+    ShapeInfo shapes[128];
+    const int ns = list_shapes(dm.dtype, shapes, 128);
+    for (int i = 0; i < ns; ++i)
+        if (shapes[i].kt == t->kt && shapes[i].mt == t->mt && shapes[i].ring == t->ring) {
+            model_cost(dm, *t, shapes[i], true, times_us);
+            return PS_OK;
+        }
+    return PS_EUNSUPPORTED;
 }
 
 extern "C" double ps_tile_cost_us(const ps_conv_desc *d, const ps_tile *t) { return cost_of(d, t, false); }

@@ -22,9 +22,8 @@ import sys
 from . import binding as ps
 from . import workloads as wl
 
-# capacity (bytes) of the levels a reuse can be served from, fastest first, and latency (s) / bandwidth (B/s) of
-# each level plus memory: registers+LDS of one compute unit, all L2 slices, Infinity Cache, HBM
-LEVEL_BYTES = [160 * 1024 + 512 * 1024, 8 * 4 * 1024 * 1024, 256 * 1024 * 1024]
+# latency (s) / bandwidth (B/s) of the levels a reuse can be served from, fastest first, plus memory: registers+LDS
+# of one compute unit, all L2 slices, Infinity Cache, HBM (their capacities are ps_tile_reuse_levels')
 LATENCY = [0.1e-6, 0.5e-6, 0.8e-6, 1.2e-6]
 BANDWIDTH = [100e12, 14e12, 9e12, 5e12]
 
@@ -49,40 +48,15 @@ def _spearman(a, b):
     return num / den if den > 0 else float("nan")
 
 
-def paper_cost(shape: wl.ConvShape, es: int, tile) -> float | None:
+def paper_cost(desc: ps.ConvDesc, tile) -> float | None:
     """Eq. 1 for one candidate tile, or None where the workgroup-level nest is not rectangular (a split that cuts
     through a c-block's taps)."""
-    kt, mt, _ring, c_split, raster = tile
-    M = shape.N * shape.P * shape.Q
-    n_mt, n_kt = -(-M // mt), -(-shape.K // kt)
-    Cb, RS = -(-shape.C // 16), shape.R * shape.S
-    if Cb % c_split:
-        return None
-    cbs = Cb // c_split
-    # loops: outer tile loop, inner tile loop (launch order), split, c-block, tap
-    ext = (n_mt, n_kt, c_split, cbs, RS) if raster == 0 else (n_kt, n_mt, c_split, cbs, RS)
-    im, ik = (0, 1) if raster == 0 else (1, 0)
-
-    def row(**kw):
-        r = [0] * 5
-        for k, v in kw.items():
-            r[{"m": im, "k": ik, "s": 2, "c": 3, "t": 4}[k]] = v
-        return tuple(r)
-    out_b = min(mt, M) * min(kt, shape.K) * 4
-    in_b = min(mt, M) * 16 * es          # one c-block of the tile's pixels (the taps re-read the same block)
-    wt_b = min(kt, shape.K) * 16 * es    # one tap of one c-block of the tile's filters
-    refs = [
-        ps.ArrayRef.of(0, (row(m=1), row(k=1), row(s=1)), None, False, out_b),   # partial tile read (accumulate)
-        ps.ArrayRef.of(0, (row(m=1), row(k=1), row(s=1)), None, True, out_b),    # ... and written
-        ps.ArrayRef.of(1, (row(m=1), row(s=cbs, c=1)), None, False, in_b),
-        ps.ArrayRef.of(2, (row(k=1), row(s=cbs, c=1), row(t=1)), None, False, wt_b),
-    ]
-    deps = ps.ps_reuse_working_sets(ext, refs)
-    ws = set()
-    for _, _, lo, hi in deps:
-        ws.add(lo)
-        ws.add(hi)
-    level, mem = ps.ps_reuse_assign(sorted(ws), LEVEL_BYTES)
+    try:
+        level, mem = ps.ps_tile_reuse_levels(desc, ps.Tile(*tile))
+    except ps.PsError as e:
+        if e.status == ps.PS_EUNSUPPORTED:
+            return None
+        raise
     return ps.ps_reuse_cost(level, mem, LATENCY, BANDWIDTH)
 
 
@@ -112,7 +86,7 @@ def report(path: str, dtype: str, with_paper_cost: bool = True, out=sys.stdout) 
             row[f"top{k}_loss"] = round(loss, 4)
             worst[k] = max(worst[k], loss)
         if with_paper_cost:
-            pc = {t: paper_cost(L, es, t) for t in meas}
+            pc = {t: paper_cost(d, t) for t in meas}
             pc = {t: c for t, c in pc.items() if c is not None}
             if pc:
                 pick = min(pc, key=pc.get)

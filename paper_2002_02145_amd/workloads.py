@@ -135,3 +135,32 @@ def bf16_bits(a_rounded: np.ndarray) -> np.ndarray:
     """The 16-bit patterns of values that are already exactly representable in bfloat16."""
     bits = np.ascontiguousarray(a_rounded, dtype=np.float32).view(np.uint32)
     return (bits >> np.uint32(16)).astype(np.uint16).reshape(a_rounded.shape)
+
+
+# ---- inputs of the pairwise ranker (Section 4.2.2): random draws only, no arithmetic of the method ----
+
+RANKER_STATS = 4
+RANKER_WIDTHS = (2 * RANKER_STATS, 64, 32, 16, 8, 2)
+
+
+def ranker_params(seed: int, scale: float = 1.0) -> np.ndarray:
+    """A random parameter vector in the flat layout of the library (per layer: weights [inputs][units], bias):
+    weights normal with standard deviation scale * sqrt(2 / inputs), biases normal with 0.1 * scale."""
+    rng = np.random.default_rng(seed)
+    parts = []
+    for a, b in zip(RANKER_WIDTHS[:-1], RANKER_WIDTHS[1:]):
+        parts.append(rng.normal(0.0, scale * math.sqrt(2.0 / a), a * b))
+        parts.append(rng.normal(0.0, 0.1 * scale, b))
+    return np.concatenate(parts).astype(np.float32)
+
+
+def ranker_stats(n: int, seed: int, zero_fraction: float = 0.2, duplicates: int = 0) -> np.ndarray:
+    """Statistics of n variants, float32 [n][4]: sizes log-uniform between 1e3 and 1e9 with a share of exact zeros
+    (a level that holds no working set), the way working-set sizes in bytes are spread; the last `duplicates` rows
+    repeat earlier ones (variants that differ in nothing the statistics see)."""
+    rng = np.random.default_rng(seed)
+    s = np.exp(rng.uniform(math.log(1e3), math.log(1e9), (n, RANKER_STATS)))
+    s[rng.uniform(size=s.shape) < zero_fraction] = 0.0
+    for d in range(min(duplicates, n // 2)):
+        s[n - 1 - d] = s[d]
+    return s.astype(np.float32)

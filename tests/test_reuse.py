@@ -115,6 +115,6 @@ def test_rank_report_on_a_synthetic_sweep(ps, tmp_path):
     row = json.loads(out.getvalue().splitlines()[0])
     assert row["eq1_candidates"] == len(rows) and -1.0 <= row["eq1_spearman"] <= 1.0
     # Eq. 1 prefers fewer bytes through the slow levels: a larger tile of the same shape family never costs more
-    small = rank_report.paper_cost(L, 4, (64, 64, 4, 1, 0))
-    large = rank_report.paper_cost(L, 4, (64, 128, 4, 1, 0))
+    small = rank_report.paper_cost(d, (64, 64, 4, 1, 0))
+    large = rank_report.paper_cost(d, (64, 128, 4, 1, 0))
     assert small is not None and large is not None and small > 0 and large > 0
