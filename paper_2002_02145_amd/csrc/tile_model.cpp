@@ -50,6 +50,7 @@ struct Chip {
     double fill_clk = 4500.0;                 // first loads of a workgroup (nothing to overlap with)
     double launch_us = 1.5;
     double dependent_launch_us = 5.0;         // a kernel that has to wait for the previous one to drain
+    double plane_latency_us = 0.3;            // per partial plane: the adding pass reads them one after another
     double reduce_ineff = 2.0;                // the plane-adding pass against streaming bandwidth
 };
 
@@ -223,7 +224,8 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         t_extra = out_bytes / c.hbm_bw * 1e6 + c.launch_us;  // the clearing pass
     } else if (t.c_split > 1) {
         t_mem += out_bytes * t.c_split / far_bw;  // partial planes written once ...
-        t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 * c.reduce_ineff + c.dependent_launch_us;  // ... and added by a second pass
+        t_extra = out_bytes * (t.c_split + 1.0) / far_bw * 1e6 * c.reduce_ineff + c.dependent_launch_us +
+                  c.plane_latency_us * t.c_split;  // ... and added by a second pass
     }
     // Filters larger than one XCD's L2: with the channel tiles fastest every XCD streams all of them through its L2
     // over and over, with the pixel tiles fastest it stays on the slices of a few channel tiles.  Where the two
