@@ -57,7 +57,8 @@ int ps_tile_level_times_ws(const ps_conv_desc *desc, const ps_tile *tile, double
  *           variant i is presented first and variant j second (the diagonal is set to zero)
  * Every ordered pair (i, j), i != j, is one game: the eight statistics of i and j are divided by their sum (all
  * zeros stay zeros) and fed to the network; the first output firing is a win for i, the second a win for j,
- * neither a draw.  All arithmetic is single precision.  n = 0 is allowed and does nothing; n above
+ * neither a draw.  All arithmetic is single precision; win counts are integer sums and do not depend on scheduling.
+ * Two kernels are enqueued (wins is cleared by a fill kernel, not a memset, so the call can be captured in a graph).  n = 0 is allowed and does nothing; n above
  * PS_RANKER_MAX_VARIANTS is PS_EUNSUPPORTED. */
 int ps_ranker_play(const float *stats, int n, const float *params, float theta, int32_t *wins, float *probs,
                    void *stream);

@@ -19,25 +19,46 @@ static_assert(kIn * kW1 + kW1 + kW1 * kW2 + kW2 + kW2 * kW3 + kW3 + kW3 * kW4 + 
               "parameter layout");
 
 // y[u] = b[u] + sum_k x[k] * W[k][u].  The parameters sit in LDS and every lane reads the same address (a
-// broadcast), four values per read; activations stay in registers.
+// broadcast), four values per read; activations stay in registers.  The weights are walked in chunks of 32 values;
+// the reads of the next chunk are issued before the multiply-adds of the current one, and scheduling fences keep
+// that order (without them the compiler hoists every read of a layer and runs out of registers).
 template <int IN, int OUT>
-__device__ __forceinline__ const float *dense(const float *__restrict__ p, const float (&x)[IN], float (&y)[OUT])
+__device__ __forceinline__ const float *dense(const float *p, const float (&x)[IN], float (&y)[OUT])
 {
-    const float *__restrict__ W = p;
-    const float *__restrict__ b = p + IN * OUT;
+    constexpr int TOT = IN * OUT, CH = 32, NCH = (TOT + CH - 1) / CH;
+    static_assert(TOT % 4 == 0, "rows are read four values at a time");
+    const float4 *W = reinterpret_cast<const float4 *>(p);
+    const float *b = p + TOT;
+    float4 buf[2][CH / 4];
+#pragma unroll
+    for (int q = 0; q < CH / 4; ++q)
+        if (q * 4 < TOT) buf[0][q] = W[q];
 #pragma unroll
     for (int u = 0; u < OUT; ++u) y[u] = b[u];
 #pragma unroll
-    for (int k = 0; k < IN; ++k) {
+    for (int c = 0; c < NCH; ++c) {
+        if (c + 1 < NCH) {
 #pragma unroll
-        for (int u = 0; u < OUT; ++u) y[u] = fmaf(x[k], W[k * OUT + u], y[u]);
-        if (k % 2 == 1) __builtin_amdgcn_sched_barrier(0);  // keeps the reads of later rows from piling up in registers
+            for (int q = 0; q < CH / 4; ++q)
+                if ((c + 1) * CH + q * 4 < TOT) buf[(c + 1) & 1][q] = W[(c + 1) * (CH / 4) + q];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) {
+            const int idx = c * CH + e;
+            if (idx < TOT) {
+                const float4 w4 = buf[c & 1][e / 4];
+                const float w = e % 4 == 0 ? w4.x : e % 4 == 1 ? w4.y : e % 4 == 2 ? w4.z : w4.w;
+                y[idx % OUT] = fmaf(x[idx / OUT], w, y[idx % OUT]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     return b + OUT;
 }
 
 // The two softmax outputs of the game "a first, b second".
-__device__ __forceinline__ float2 play(const float *__restrict__ params, const float4 a, const float4 b)
+__device__ __forceinline__ float2 play(const float *params, const float4 a, const float4 b)
 {
     float x[kIn] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
     float total = 0.f;
@@ -66,38 +87,37 @@ __device__ __forceinline__ float2 play(const float *__restrict__ params, const f
     return make_float2(e0 / s, e1 / s);
 }
 
-// Workgroup i tallies variant i: its lanes take the opponents j in turn and play both seatings, (i, j) and (j, i).
-// Every game is therefore evaluated by both of its players' workgroups, which keeps the tally free of atomics and
-// its result independent of scheduling.
+__global__ __launch_bounds__(256) void ranker_clear_kernel(int32_t *__restrict__ wins, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) wins[i] = 0;
+}
+
+// One lane per game: workgroup (x, y) plays variant i = y, presented first, against the 256 variants
+// j = 256 x .. 256 x + 255, one per lane.  A first output that fires is a win for i: counted over the wave and added
+// once; a second output that fires is a win for the lane's own j.  Integer additions commute, so the counts do not
+// depend on the order in which workgroups finish.  wins must be zero on entry (ranker_clear_kernel).
 __global__ __launch_bounds__(256) void ranker_tournament_kernel(const float4 *__restrict__ stats, int n,
                                                                 const float *__restrict__ params, float theta,
                                                                 int32_t *__restrict__ wins, float2 *__restrict__ probs)
 {
     __shared__ __attribute__((aligned(16))) float net[PS_RANKER_PARAMS + 2];
-    __shared__ int partial[4];
     for (int k = threadIdx.x; k < PS_RANKER_PARAMS; k += 256) net[k] = params[k];
     __syncthreads();
-    const int i = blockIdx.x;
+    const int i = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j - (int)(threadIdx.x & 63) >= n) return;  // the whole wave lies beyond the last variant
+    const bool live = j < n && j != i;
     const float4 mine = stats[i];
-    int won = 0;
-    for (int j = threadIdx.x; j < n; j += 256) {
-        if (j == i) {
-            if (probs) probs[(size_t)i * n + j] = make_float2(0.f, 0.f);
-            continue;
-        }
-        const float4 other = stats[j];
-#pragma unroll 1
-        for (int seat = 0; seat < 2; ++seat) {  // one copy of the network's code serves both seatings
-            const float2 out = play(net, seat == 0 ? mine : other, seat == 0 ? other : mine);
-            if (seat == 0 && probs) probs[(size_t)i * n + j] = out;
-            won += (seat == 0 ? out.x : out.y) > theta ? 1 : 0;  // theta >= 0.5: at most one output fires
-        }
-    }
+    const float4 other = live ? stats[j] : mine;
+    const float2 out = play(net, mine, other);
+    if (probs && j < n) probs[(size_t)i * n + j] = live ? out : make_float2(0.f, 0.f);
+    // theta >= 0.5: at most one of the two outputs fires
+    int first = live && out.x > theta ? 1 : 0;
+    if (live && out.y > theta) atomicAdd(&wins[j], 1);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) won += __shfl_down(won, off, 64);
-    if ((threadIdx.x & 63) == 0) partial[threadIdx.x >> 6] = won;
-    __syncthreads();
-    if (threadIdx.x == 0) wins[i] = partial[0] + partial[1] + partial[2] + partial[3];
+    for (int off = 32; off > 0; off >>= 1) first += __shfl_down(first, off, 64);
+    if ((threadIdx.x & 63) == 0 && first > 0) atomicAdd(&wins[i], first);
 }
 
 }  // namespace
@@ -111,7 +131,10 @@ extern "C" int ps_ranker_play(const float *stats, int n, const float *params, fl
     if (!stats || !params || !wins) return PS_EINVAL;
     if (n > PS_RANKER_MAX_VARIANTS) return PS_EUNSUPPORTED;
     if (!ps::aligned16(stats) || (probs && (reinterpret_cast<uintptr_t>(probs) & 7u))) return PS_EINVAL;
-    hipLaunchKernelGGL(ps::ranker_tournament_kernel, dim3((unsigned)n), dim3(256), 0, static_cast<hipStream_t>(stream),
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const unsigned chunks = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(ps::ranker_clear_kernel, dim3(chunks), dim3(256), 0, st, wins, n);
+    hipLaunchKernelGGL(ps::ranker_tournament_kernel, dim3(chunks, (unsigned)n), dim3(256), 0, st,
                        reinterpret_cast<const float4 *>(stats), n, params, theta, wins, reinterpret_cast<float2 *>(probs));
     return ps::hip_status(hipGetLastError());
 }

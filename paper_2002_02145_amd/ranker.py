@@ -239,8 +239,8 @@ def evaluate(dtype: str, kind: int, out=sys.stdout) -> dict:
                "top3_vs_best": round(min(us[t] for t, _ in ranked) / best - 1.0, 4),
                "model_pick_vs_best": round(us.get(model_pick.as_tuple(), float("nan")) / best - 1.0, 4),
                "candidates": len(tiles), "rank_call_ms": round(rank_ms, 2), "tournament_us": round(play_us, 1),
-               # two seatings per pair, each evaluated by both players' workgroups; 2 flop per parameter
-               "tournament_gflops": round(4.0 * len(tiles) * (len(tiles) - 1) * 2 * ps.PS_RANKER_PARAMS / play_us / 1e3, 1)}
+               # n (n - 1) games, 2 flop per parameter each
+               "tournament_gflops": round(len(tiles) * (len(tiles) - 1) * 2.0 * ps.PS_RANKER_PARAMS / play_us / 1e3, 1)}
         worst, worst_model = max(worst, row["pick_vs_best"]), max(worst_model, row["model_pick_vs_best"])
         rows.append(row)
         print(json.dumps(row), file=out)
