@@ -244,12 +244,15 @@ extern "C" int ps_tile_rank_dnn(const ps_conv_desc *desc, size_t workspace_bytes
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *d_stats = static_cast<float *>(scratch);
     int32_t *d_wins = reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + stats_bytes);
-    if (int rc = ps::hip_status(hipMemcpyAsync(d_stats, stats.data(), stats_bytes, hipMemcpyHostToDevice, st))) return rc;
-    if (int rc = ps_ranker_play(d_stats, n, params, theta, d_wins, nullptr, stream)) return rc;
+    // The copies use this function's own host buffers, so every path out of here waits for the stream first.
     std::vector<int32_t> won((size_t)n);
-    if (int rc = ps::hip_status(hipMemcpyAsync(won.data(), d_wins, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st)))
-        return rc;
-    if (int rc = ps::hip_status(hipStreamSynchronize(st))) return rc;
+    int rc = ps::hip_status(hipMemcpyAsync(d_stats, stats.data(), stats_bytes, hipMemcpyHostToDevice, st));
+    if (rc == PS_OK) rc = ps_ranker_play(d_stats, n, params, theta, d_wins, nullptr, stream);
+    if (rc == PS_OK)
+        rc = ps::hip_status(hipMemcpyAsync(won.data(), d_wins, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    const int rc_sync = ps::hip_status(hipStreamSynchronize(st));
+    if (rc != PS_OK) return rc;
+    if (rc_sync != PS_OK) return rc_sync;
 
     std::vector<int> order((size_t)n);
     std::iota(order.begin(), order.end(), 0);

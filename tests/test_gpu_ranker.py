@@ -133,3 +133,27 @@ def test_ranking_of_a_layers_tiles_matches_the_oracle(kind, layer):
     assert [t.as_tuple() for t, _ in got] == [tiles[i].as_tuple() for i in ro.ranking(wins)]
     top3 = ps.ps_tile_rank_dnn(d, 1 << 30, kind, pd, ro.THETA, scratch, scratch.numel(), 3)
     assert [(t.as_tuple(), w) for t, w in top3] == [(t.as_tuple(), w) for t, w in got[:3]]
+
+
+def test_tournament_replays_correctly_from_a_captured_graph():
+    """The call enqueues two kernels and no memset; captured once and replayed on changing statistics it must give
+    what the eager call gives, on every replay."""
+    n = 200
+    params = torch.from_numpy(wl.ranker_params(31, 4.0)).to(DEV)
+    stats = torch.from_numpy(wl.ranker_stats(n, 32)).to(DEV)
+    wins = torch.zeros(n, dtype=torch.int32, device=DEV)
+    eager = torch.zeros(n, dtype=torch.int32, device=DEV)
+    ps.ps_ranker_play(stats, n, params, 0.6, wins)            # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ps.ps_ranker_play(stats, n, params, 0.6, wins)
+    for replay in range(4):
+        stats.copy_(torch.from_numpy(wl.ranker_stats(n, 40 + replay)).to(DEV))
+        wins.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        ps.ps_ranker_play(stats, n, params, 0.6, eager)
+        torch.cuda.synchronize()
+        assert torch.equal(wins, eager), f"replay {replay}"
+        assert int(eager.max()) > 0
