@@ -1,0 +1,43 @@
+"""The tile model's pick against the exhaustive sweeps stored with the package (measured on an MI355X; tile and
+microseconds per candidate).  Host only: the model is evaluated here, the measurements are read from the files.
+The target is a pick within 10 % of the sweep's best at the batch size of the benchmark (N = 28); the sweeps at
+N = 8 and N = 1 guard against a model that only fits the batch size it was calibrated at."""
+import json
+import os
+
+import pytest
+
+from paper_2002_02145_amd import binding as ps
+from paper_2002_02145_amd import ranker
+
+DATA = os.path.join(os.path.dirname(ranker.__file__), "data")
+
+
+def _losses(fname, dtype):
+    out = {}
+    for line in open(os.path.join(DATA, fname)):
+        r = json.loads(line)
+        d = ps.ConvDesc.of(ranker._named_layers(r["N"])[r["layer"]], dtype)
+        us = {tuple(row[:5]): row[5] for row in r["rows"]}
+        cost = {t: ps.ps_tile_cost_ws_us(d, ps.Tile(*t)) for t in us}
+        assert all(c > 0 for c in cost.values()), f"{r['layer']}: a stored tile is no longer valid"
+        # the stored sweep covers exactly the candidates the library enumerates today
+        now = {ps.ps_tile_get(d, i).as_tuple() for i in range(ps.ps_tile_count(d))}
+        assert now == set(us), f"{r['layer']}: candidate set changed since the sweep was stored"
+        pick, _ = ps.ps_tile_select_ws(d, 1 << 40)
+        assert cost[pick.as_tuple()] == min(cost.values())
+        out[r["layer"]] = us[pick.as_tuple()] / min(us.values()) - 1.0
+    return out
+
+
+@pytest.mark.parametrize("fname,dtype,worst,mean", [
+    ("sweep_f32_N28.jsonl", ps.PS_F32, 0.10, 0.02),
+    ("sweep_bf16_N28.jsonl", ps.PS_BF16, 0.10, 0.03),
+    ("sweep_f32_N8.jsonl", ps.PS_F32, 0.12, 0.04),
+    ("sweep_f32_N1.jsonl", ps.PS_F32, 0.10, 0.03),
+])
+def test_pick_is_close_to_the_sweeps_best(fname, dtype, worst, mean):
+    loss = _losses(fname, dtype)
+    assert len(loss) == 14
+    assert max(loss.values()) <= worst, sorted(loss.items(), key=lambda kv: -kv[1])[:3]
+    assert sum(loss.values()) / len(loss) <= mean
