@@ -164,3 +164,24 @@ def ranker_stats(n: int, seed: int, zero_fraction: float = 0.2, duplicates: int 
     for d in range(min(duplicates, n // 2)):
         s[n - 1 - d] = s[d]
     return s.astype(np.float32)
+
+
+def random_shapes(count: int, seed: int) -> list[ConvShape]:
+    """Seeded small convolution shapes that wander over the whole parameter space the library accepts: channel
+    counts that are not multiples of 16, non-square images and filters up to 7 x 7, strides 1-3, pads 0-3 (also
+    larger than the filter needs, which gives outputs that see nothing but padding)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        if rng.uniform() < 0.5:
+            S = R
+        stride, pad = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        H, W = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        N = int(rng.integers(1, 4))
+        C = int(rng.choice([1, 3, 4, 5, 16, 17, 32, 40, 64, 70]))
+        K = 16 * int(rng.integers(1, 9))
+        out.append(ConvShape(N, C, H, W, K, R, S, stride, pad, f"random{len(out)}_seed{seed}"))
+    return out

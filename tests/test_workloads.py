@@ -47,3 +47,10 @@ def test_bf16_rounding_matches_torch_and_ties_to_even():
     assert got.view(np.uint32)[-5] == 0x3F800000 and got.view(np.uint32)[-4] == 0x3F820000
     assert np.all(wl.bf16_bits(got).astype(np.uint32) << 16 == got.view(np.uint32))
     assert np.isnan(wl.round_to_bf16(np.array([np.nan], np.float32)))[0]
+
+
+def test_random_shapes_are_seeded_and_valid():
+    a, b = wl.random_shapes(20, 5), wl.random_shapes(20, 5)
+    assert a == b and a != wl.random_shapes(20, 6)
+    for s in a:
+        assert s.K % 16 == 0 and s.P >= 1 and s.Q >= 1 and 1 <= s.stride <= 3 and 0 <= s.pad <= 3
