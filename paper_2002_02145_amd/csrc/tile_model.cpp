@@ -216,7 +216,9 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         beyond_l2 += refetch * std::min(1.0, (xcd_ws - c.l2_bytes) / xcd_ws);
     }
     const double far_bw = total <= 0.7 * c.mall_bytes ? c.mall_bw : c.hbm_bw;
-    const double t_near = cu_bytes / c.l2_bw, t_far = beyond_l2 / far_bw;
+    // L2 -> LDS is a per-compute-unit rate (the chip-wide figure over all of them): the compute unit with the most
+    // workgroups decides, which on an under-filled grid is far more than an even share.
+    const double t_near = (cu_bytes / nwg) * std::max(1.0, nwg / c.cus) / (c.l2_bw / c.cus), t_far = beyond_l2 / far_bw;
     double t_mem = std::max(t_near, t_far);
     double t_extra = 0.0;
     if (t.c_split > 1 && !with_ws) {

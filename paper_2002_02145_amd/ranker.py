@@ -40,7 +40,7 @@ DATA = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data")
 KINDS = {"working_sets": ps.PS_RANKER_WORKING_SETS, "level_times": ps.PS_RANKER_LEVEL_TIMES}
 WIDTHS = (2 * ps.PS_RANKER_STATS, 64, 32, 16, 8, 2)
 THETA = 0.6                      # Section 4.2.2
-SWEEPS = {"f32": ("sweep_f32_N28.jsonl", "sweep_f32_N8.jsonl", "sweep_f32_N1.jsonl"), "bf16": ("sweep_bf16_N28.jsonl",)}
+SWEEPS = {"f32": ("sweep_f32_N28.jsonl", "sweep_f32_N8.jsonl", "sweep_f32_N1.jsonl"), "bf16": ("sweep_bf16_N28.jsonl", "sweep_bf16_N8.jsonl", "sweep_bf16_N1.jsonl")}
 NOISE = 0.02                     # pairs closer than this are not used for training
 
 
