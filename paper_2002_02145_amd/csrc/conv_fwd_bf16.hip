@@ -92,6 +92,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WK, wm = wave / WK;
     const int half = lane >> 5, l32 = lane & 31;
+    const int lhalf = (lane & 1) ^ ((lane >> 4) & 1);  // which half of its pixel this lane loads (see the loader)
 
     const TileCoord tc = decode_tile(a);
     const int m0 = tc.mtile * MT;
@@ -102,7 +103,10 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(a.in, a.in_bytes);
     const __amdgpu_buffer_rsrc_t rwt = make_rsrc(a.wt, a.wt_bytes);
 
-    // ---- loader bookkeeping: one load fills 32 pixels (lane -> pixel lane/2, 16-byte half lane%2) ----
+    // ---- loader bookkeeping: one load fills 32 pixels (lane -> pixel lane/2, 16-byte half lane%2).  In every second
+    // group of 8 pixels the two halves of a pixel change places in LDS: the 16 lanes an LDS read serves together
+    // (16 neighbouring pixels, one half) are 32 bytes apart and would hit every bank twice; with the swap pixels
+    // p and p + 8 use different banks.  Neighbouring lanes still fetch one pixel's 32 contiguous bytes. ----
     int poff[APW], h0[APW], w0[APW];
 #pragma unroll
     for (int i = 0; i < APW; ++i) {
@@ -137,7 +141,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
             for (int i = 0; i < APW; ++i) {
                 const int grp = i * NW + wave;
                 const bool ok = bv & ((unsigned)(h0[i] + lr) < (unsigned)a.H) & ((unsigned)(w0[i] + ls) < (unsigned)a.W);
-                const unsigned off = ok ? (unsigned)((poff[i] + tapoff) * 32 + (lane & 1) * 16) : kOobOffset;
+                const unsigned off = ok ? (unsigned)((poff[i] + tapoff) * 32 + lhalf * 16) : kOobOffset;
                 char *dst = (Sh::PGRP % NW == 0 || grp < Sh::PGRP) ? abase + grp * 1024 : lds + NBUF * Sh::SLOT;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rin, (lds_ptr_t)dst, 16, off, 0, 0, 0);
             }
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
             for (int t = 0; t < TAPS; ++t) {
                 const int r = t / SIDE, sx = t % SIDE;
                 const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W);
-                vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 32 + (lane & 1) * 16) : kOobOffset;
+                vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 32 + lhalf * 16) : kOobOffset;
             }
 #pragma unroll
         for (int i = 0; i < WPW; ++i) {
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
     // ---- reader bookkeeping -------------------------------------------------------------------
     int paddr[TM], waddr[TK];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) paddr[tm] = ((wm * TM + tm) * 32 + l32) * 32 + half * 16;
+    for (int tm = 0; tm < TM; ++tm) paddr[tm] = ((wm * TM + tm) * 32 + l32) * 32 + (half ^ ((l32 >> 3) & 1)) * 16;
 #pragma unroll
     for (int tk = 0; tk < TK; ++tk) {
         const int ofm = (wk * TK + tk) * 32 + l32;

@@ -10,8 +10,13 @@
 // Patch layout: "extended rows".  Image n owns extended rows n*(H+2) .. n*(H+2)+H+1: a zero row, its H rows, a
 // zero row.  A tile of consecutive (n, p, q) pixels covers a contiguous range of extended rows e0 .. e1 (one more
 // on either side of its first and last pixel), also across image boundaries, and patch row e - e0 holds
-// extended row e with a zero column on either side: pitch W + 2 pixels of 32 bytes.  Pixel (n, p, q) has its
+// extended row e with a zero column on either side: pitch W + 2 pixels.  Pixel (n, p, q) has its
 // centre at row n*(H+2) + p + 1 - e0, column q + 1, and tap (r, s) at (r - 1) rows and (s - 1) columns from it.
+// Patch pixels are numbered row by row, 32 bytes each; in every second group of 8 pixels the two 16-byte channel
+// halves of a pixel change places.  (The 16 lanes that an LDS read serves in one go -- 16 neighbouring pixels, one
+// channel half -- are 32 bytes apart and would hit every bank twice: the bank-conflict counter read 39 % of the LDS
+// cycles.  With the swap, pixels p and p + 8 use different banks, and neighbouring lanes of a load still fetch one
+// pixel's 32 contiguous bytes.)
 // The loads place 16 bytes per lane at consecutive LDS addresses, so the layout is produced by choosing each
 // lane's global address (out of range = zero fill) for the LDS position it writes.
 #pragma once
@@ -102,14 +107,16 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_halo_kernel(const 
     unsigned vh[HPW], vw[WPW];
 #pragma unroll
     for (int i = 0; i < HPW; ++i) {
-        const int j = (i * NW + wave) * 64 + lane;  // 16-byte position inside the patch
-        const int px = j >> 1;
+        // 16-byte position inside the patch: pixel j / 2; in every second group of 8 pixels the two halves of a
+        // pixel change places (see the layout note at the top)
+        const int j = (i * NW + wave) * 64 + lane;
+        const int px = j >> 1, sub = (j & 1) ^ ((px >> 3) & 1);
         int hr, hc, n, pe;
         fast_divmod(px, pitch, a.magic_pitch, hr, hc);
         fast_divmod(e0 + hr, h2, a.magic_h2, n, pe);
         pe -= 1;
         const bool ok = (hr < nrows) & ((unsigned)pe < (unsigned)a.H) & ((unsigned)(hc - 1) < (unsigned)a.W);
-        vh[i] = ok ? (unsigned)(((n * a.Cb * a.H + pe) * a.W + hc - 1) * 32 + (j & 1) * 16) : kOobOffset;
+        vh[i] = ok ? (unsigned)(((n * a.Cb * a.H + pe) * a.W + hc - 1) * 32 + sub * 16) : kOobOffset;
     }
 #pragma unroll
     for (int i = 0; i < WPW; ++i) {
@@ -134,9 +141,12 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_halo_kernel(const 
         int n, pq, p, q;
         fast_divmod(m, a.PQ, a.magic_pq, n, pq);
         fast_divmod(pq, a.Q, a.magic_q, p, q);
-        const int centre = ((n * h2 + p + 1 - e0) * pitch + q + 1) * 32 + half * 16;
+        const int centre = (n * h2 + p + 1 - e0) * pitch + q + 1;  // patch pixel
 #pragma unroll
-        for (int t = 0; t < 9; ++t) paddr[tm][t] = centre + ((t / 3 - 1) * pitch + (t % 3 - 1)) * 32;
+        for (int t = 0; t < 9; ++t) {
+            const int px = centre + (t / 3 - 1) * pitch + (t % 3 - 1);
+            paddr[tm][t] = px * 32 + (half ^ ((px >> 3) & 1)) * 16;
+        }
     }
 #pragma unroll
     for (int tk = 0; tk < TK; ++tk) {
