@@ -157,3 +157,23 @@ def test_tournament_replays_correctly_from_a_captured_graph():
         torch.cuda.synchronize()
         assert torch.equal(wins, eager), f"replay {replay}"
         assert int(eager.max()) > 0
+
+
+def test_ranking_respects_the_workspace_limit_and_runs_in_bf16():
+    """With no workspace only unsplit tiles may be ranked; the statistics of both kinds exist for 16-bit descriptors."""
+    from paper_2002_02145_amd import ranker
+    L = wl.resnet50_layers()[3]                               # 3x3, 512 channels, 7x7: many split candidates
+    d = ps.ConvDesc.of(L, ps.PS_BF16)
+    for kind in (ps.PS_RANKER_LEVEL_TIMES, ps.PS_RANKER_WORKING_SETS):
+        params = torch.from_numpy(ranker.load_params(kind, "bf16")).to(DEV)
+        scratch = torch.empty(ps.ps_tile_rank_dnn_scratch_bytes(d), dtype=torch.uint8, device=DEV)
+        everything = ps.ps_tile_rank_dnn(d, 1 << 40, kind, params, ro.THETA, scratch, scratch.numel(), 10000)
+        unsplit = ps.ps_tile_rank_dnn(d, 0, kind, params, ro.THETA, scratch, scratch.numel(), 10000)
+        assert any(t.c_split > 1 for t, _ in everything)
+        assert unsplit and all(t.c_split == 1 for t, _ in unsplit) and len(unsplit) < len(everything)
+        tiles, stats = ranker.tile_stats(d, kind, workspace_bytes=0)
+        assert sorted(t.as_tuple() for t, _ in unsplit) == sorted(t.as_tuple() for t in tiles)
+        o_wins, _ = ro.tournament(stats.astype(np.float64), ro.unpack(params.cpu().numpy()), ro.THETA)
+        got = {t.as_tuple(): w for t, w in unsplit}
+        close = sum(abs(got[t.as_tuple()] - int(w)) for t, w in zip(tiles, o_wins))
+        assert close <= max(2, len(tiles) // 20)              # games within rounding of the threshold may fall either way
