@@ -94,7 +94,8 @@ int ps_blocked_to_nkpq(const ps_conv_desc *d, const void *oblk, void *nkpq, void
 
 /* ---- forward convolution ------------------------------------------------------------- */
 /* out_blk = conv(in_blk, wt_blk) on blocked tensors; out_blk is overwritten (the "+=" of
- * Fig. 4 applied to a cleared output).  The workgroup tile is the tile model's pick. */
+ * Fig. 4 applied to a cleared output).  The workgroup tile is the tile model's pick (ps_tile_pick: ranked once per
+ * descriptor, then served from the per-process table). */
 int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const void *wt_blk, void *out_blk,
                   void *stream);
 /* Same with an explicit tile (autotune sweeps).  PS_EUNSUPPORTED if ps_tile_valid fails. */
@@ -152,6 +153,18 @@ int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *be
  * written (fewer than k if the layer has fewer candidates), or a negative ps_status.  tiles[0] is the tile
  * ps_tile_select_ws returns.  Timing the k tiles is the caller's part (paper_2002_02145_amd.autotune.run_top_k). */
 int ps_tile_rank_ws(const ps_conv_desc *d, size_t workspace_bytes, int k, ps_tile *tiles, double *modelled_us);
+
+/* The tile the convolution calls run when none is passed: ps_conv2d_fwd (with_workspace = 0, ranking of
+ * ps_tile_select) or ps_conv2d_fwd_ws / ps_conv2d_fwd_fused with t == NULL (with_workspace != 0, ranking of
+ * ps_tile_select_ws for `workspace_bytes`).  The ranking of Section 4.2 depends on the descriptor alone, so the
+ * library computes it on first use and keeps it, together with the prepared launch of every (descriptor, tile) pair
+ * it has run, in a per-process table: entries are immutable once published, lookups are thread-safe, steady-state
+ * cost is a hash lookup instead of pricing every candidate.  What a workspace size decides is how many partial planes
+ * fit (at most 16), so sizes with the same count share an entry.  The table holds at most 16384 entries of each
+ * kind; beyond that, results are computed per call as ps_tile_select does.  ps_tile_cache_entries reports how many
+ * entries (picks plus prepared launches) the process holds. */
+int ps_tile_pick(const ps_conv_desc *d, int with_workspace, size_t workspace_bytes, ps_tile *t);
+size_t ps_tile_cache_entries(void);
 
 /* Which inner loop the library runs for tile `t` on `d` (for reports and tests): the loop with a runtime filter size,
  * the loops with a 1x1 or 3x3 filter baked in, the 7x7 loop that packs four taps of up to four channels into one

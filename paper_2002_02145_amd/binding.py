@@ -106,6 +106,8 @@ def _load() -> ctypes.CDLL:
         "ps_conv2d_fwd_ws": (ctypes.c_int, [dp, tp, vp, vp, vp, vp, ctypes.c_size_t, vp]),
         "ps_conv2d_fwd_fused": (ctypes.c_int, [dp, tp, ctypes.POINTER(Epilogue), vp, vp, vp, vp, ctypes.c_size_t, vp]),
         "ps_tile_kernel": (ctypes.c_int, [dp, tp]),
+        "ps_tile_pick": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_size_t, tp]),
+        "ps_tile_cache_entries": (ctypes.c_size_t, []),
         "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_probe_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]),
@@ -240,6 +242,18 @@ def ps_tile_kernel(desc: ConvDesc, tile: Tile) -> int:
     if v < 0:
         raise PsError(v, "ps_tile_kernel")
     return v
+
+
+def ps_tile_pick(desc: ConvDesc, with_workspace: bool = False, workspace_bytes: int = 0) -> Tile:
+    """The tile the convolution calls run when none is passed (cached per descriptor inside the library)."""
+    t = Tile()
+    _check(lib.ps_tile_pick(ctypes.byref(desc), int(bool(with_workspace)), int(workspace_bytes), ctypes.byref(t)),
+           "ps_tile_pick")
+    return t
+
+
+def ps_tile_cache_entries() -> int:
+    return int(lib.ps_tile_cache_entries())
 
 
 def ps_tile_cost_ws_us(desc: ConvDesc, tile: Tile) -> float:

@@ -1,5 +1,9 @@
 // C ABI entry points: descriptor validation, size queries, convolution launch.
 #include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <shared_mutex>
+#include <unordered_map>
 
 #include "conv_fwd_kernel.h"
 
@@ -51,7 +55,7 @@ const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 }
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary, lds_3x3, lds_halo;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -60,7 +64,8 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     const ShapeEntry *tab = dtype == PS_F32 ? f32_shapes(&n) : bf16_shapes(&n);
     n = n < cap ? n : cap;
     for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group,
-                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0, tab[i].launch == nullptr, tab[i].stationary};
+                                                   tab[i].launch_halo ? tab[i].halo_bytes : 0, tab[i].launch == nullptr, tab[i].stationary,
+                                                   tab[i].lds_3x3, tab[i].lds_halo};
     return n;
 }
 
@@ -117,15 +122,27 @@ int kernel_variant(const Dims &dm, const ps_tile &t, const ShapeEntry &sh)
     return PS_KERNEL_GENERAL;
 }
 
-int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt, float *out, float *ws, hipStream_t st,
-                const float *bias = nullptr, int epi = 0)
+// Everything a launch of tile `t` on one descriptor needs, prepared once: which loop runs, its grid and its
+// arguments except the caller's pointers.
+struct Plan {
+    Dims dm;
+    ps_tile t;
+    ConvArgs a;
+    LaunchFn fn;
+    unsigned grid;
+    int variant;
+    size_t ws_need;  // bytes of partial planes a split reduction stores when a workspace is lent
+};
+
+int build_plan(const Dims &dm, const ps_tile &t, Plan *pl)
 {
     int rc = tile_valid(dm, t);
     if (rc != PS_OK) return rc;
     const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.ring);
-    ConvArgs a;
-    a.in = in; a.wt = wt; a.out = out;
-    a.bias = bias; a.epi = epi;
+    pl->dm = dm;
+    pl->t = t;
+    ConvArgs &a = pl->a;
+    a = ConvArgs{};
     a.cin = dm.C;
     a.H = dm.H; a.W = dm.W; a.Cb = dm.Cb; a.Kb = dm.Kb; a.R = dm.R; a.S = dm.S;
     a.stride = dm.stride; a.pad = dm.pad; a.Q = dm.Q;
@@ -140,37 +157,159 @@ int conv_launch(const Dims &dm, const ps_tile &t, const void *in, const void *wt
     a.in_bytes = (unsigned)((size_t)dm.N * dm.Cb * dm.H * dm.W * kBlock * dm.es);
     a.wt_bytes = (unsigned)((size_t)dm.Kb * dm.NB * kBlock * kBlock * dm.es);
     a.out_elems = dm.M * dm.K;
-    a.partial = t.c_split > 1 ? ws : nullptr;
-    if (t.c_split > 1 && !ws) {
-        rc = launch_fill_zero(out, (size_t)dm.M * dm.K, st);
-        if (rc != PS_OK) return rc;
-    }
     a.plane_bytes = dm.H * dm.W * kBlock * dm.es;
     const auto magic = [](int d) { return d == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)d); };
     a.magic_split = magic(a.c_split);
     a.magic_pitch = magic(dm.W + 2);
     a.magic_h2 = magic(dm.H + 2);
     a.magic_inner = magic(a.raster == 0 ? a.n_kt : a.n_mt);
-    a.magic_pq = a.PQ == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.PQ);
-    a.magic_q = a.Q == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / (unsigned)a.Q);
+    a.magic_pq = magic(a.PQ);
+    a.magic_q = magic(a.Q);
     a.out_bytes = (unsigned)((size_t)dm.M * dm.K * 4);
-    LaunchFn fn = sh->launch;
-    switch (kernel_variant(dm, t, *sh)) {
+    pl->variant = kernel_variant(dm, t, *sh);
+    pl->fn = sh->launch;
+    switch (pl->variant) {
     case PS_KERNEL_1X1:
-    case PS_KERNEL_STATIONARY_1X1: fn = sh->launch_1x1; break;
-    case PS_KERNEL_3X3: fn = sh->launch_3x3; break;
-    case PS_KERNEL_PATCH_3X3: fn = sh->launch_halo; break;
+    case PS_KERNEL_STATIONARY_1X1: pl->fn = sh->launch_1x1; break;
+    case PS_KERNEL_3X3: pl->fn = sh->launch_3x3; break;
+    case PS_KERNEL_PATCH_3X3: pl->fn = sh->launch_halo; break;
     case PS_KERNEL_PACKED_7X7:
-        fn = sh->launch_7x7p;
+        pl->fn = sh->launch_7x7p;
         a.nb_split = 13;  // 49 taps, four per batch element; a.NB stays 49 for filter addressing
         break;
     default: break;
     }
-    fn(a, (unsigned)(a.n_mt * a.n_kt * a.c_split), st);
+    pl->grid = (unsigned)(a.n_mt * a.n_kt * a.c_split);
+    pl->ws_need = t.c_split > 1 ? (size_t)t.c_split * (size_t)dm.M * dm.K * 4 : 0;
+    return PS_OK;
+}
+
+// ---- per-process caches -------------------------------------------------------------------------------------
+// Tile selection enumerates and prices every candidate (tens of microseconds, as long as the kernels it
+// selects for), and preparing a launch walks the shape table and, for the patch kernels, every pixel tile.  Both
+// depend on the descriptor alone, so each result is computed on first use and kept for the life of the process:
+// entries are never changed or removed once published, readers take a shared lock, and a full table simply stops
+// taking new entries (the call then computes its answer as before).
+struct CacheKey {
+    int32_t v[16];
+    bool operator==(const CacheKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
+};
+struct CacheKeyHash {
+    size_t operator()(const CacheKey &k) const
+    {
+        uint64_t h = 1469598103934665603ull;  // FNV-1a over the words
+        for (int i = 0; i < 16; ++i) h = (h ^ (uint32_t)k.v[i]) * 1099511628211ull;
+        return (size_t)h;
+    }
+};
+
+template <class V>
+class FrozenCache {
+public:
+    const V *find(const CacheKey &k)
+    {
+        std::shared_lock<std::shared_mutex> lk(mu_);
+        auto it = map_.find(k);
+        return it == map_.end() ? nullptr : &it->second;  // node addresses survive rehashing
+    }
+    // Publishes `v` unless another thread got there first; returns the published entry (nullptr if the table is full).
+    const V *publish(const CacheKey &k, const V &v)
+    {
+        std::unique_lock<std::shared_mutex> lk(mu_);
+        auto it = map_.find(k);
+        if (it != map_.end()) return &it->second;
+        if (map_.size() >= kMaxEntries) return nullptr;
+        return &map_.emplace(k, v).first->second;
+    }
+    size_t size()
+    {
+        std::shared_lock<std::shared_mutex> lk(mu_);
+        return map_.size();
+    }
+
+private:
+    static constexpr size_t kMaxEntries = 1 << 14;
+    std::shared_mutex mu_;
+    std::unordered_map<CacheKey, V, CacheKeyHash> map_;
+};
+
+struct Pick {
+    ps_tile t;
+    double modelled_us;
+};
+
+FrozenCache<Pick> &pick_cache()
+{
+    static FrozenCache<Pick> c;
+    return c;
+}
+FrozenCache<Plan> &plan_cache()
+{
+    static FrozenCache<Plan> c;
+    return c;
+}
+
+CacheKey key_of(const ps_conv_desc &d)
+{
+    CacheKey k{};
+    const int32_t f[10] = {d.N, d.C, d.H, d.W, d.K, d.R, d.S, d.stride, d.pad, d.dtype};
+    std::memcpy(k.v, f, sizeof(f));
+    return k;
+}
+
+// The pick for a descriptor: mode 0 = ps_tile_select (split reductions by atomics), mode 1 = ps_tile_select_ws.  What a
+// workspace size decides is how many partial planes fit (splits go up to 16), so that count is the key, not the
+// byte count.
+int cached_pick(const ps_conv_desc *d, const Dims &dm, int mode, size_t ws_bytes, ps_tile *t)
+{
+    CacheKey k = key_of(*d);
+    k.v[10] = mode;
+    k.v[11] = mode ? (int32_t)std::min<size_t>(16, ws_bytes / ((size_t)dm.M * dm.K * 4)) : 0;
+    if (const Pick *p = pick_cache().find(k)) {
+        *t = p->t;
+        return PS_OK;
+    }
+    Pick p;
+    const int rc = mode ? ps_tile_select_ws(d, ws_bytes, &p.t, &p.modelled_us) : ps_tile_select(d, &p.t, &p.modelled_us);
+    if (rc != PS_OK) return rc;
+    pick_cache().publish(k, p);
+    *t = p.t;
+    return PS_OK;
+}
+
+// The prepared launch of tile `t` on `d`; *storage is used when the cache cannot take it.
+int cached_plan(const ps_conv_desc *d, const Dims &dm, const ps_tile &t, Plan *storage, const Plan **out)
+{
+    CacheKey k = key_of(*d);
+    k.v[10] = t.kt; k.v[11] = t.mt; k.v[12] = t.ring; k.v[13] = t.c_split; k.v[14] = t.raster;
+    k.v[15] = 1;  // never equal to a pick's key
+    if ((*out = plan_cache().find(k))) return PS_OK;
+    const int rc = build_plan(dm, t, storage);
+    if (rc != PS_OK) return rc;
+    const Plan *pub = plan_cache().publish(k, *storage);
+    *out = pub ? pub : storage;
+    return PS_OK;
+}
+
+int run_plan(const Plan &pl, const void *in, const void *wt, float *out, float *ws, hipStream_t st,
+             const float *bias = nullptr, int epi = 0)
+{
+    ConvArgs a = pl.a;
+    a.in = in; a.wt = wt; a.out = out;
+    a.bias = bias; a.epi = epi;
+    const bool split = pl.t.c_split > 1;
+    a.partial = split ? ws : nullptr;
+    int rc;
+    if (split && !ws) {
+        rc = launch_fill_zero(out, (size_t)pl.dm.M * pl.dm.K, st);
+        if (rc != PS_OK) return rc;
+    }
+    pl.fn(a, pl.grid, st);
     rc = hip_status(hipGetLastError());
     if (rc != PS_OK) return rc;
-    if (t.c_split > 1 && ws)
-        rc = launch_reduce_planes(ws, out, (size_t)dm.M * dm.K, t.c_split, bias, epi, dm.P * dm.Q, dm.Kb, st);
+    if (split && ws)
+        rc = launch_reduce_planes(ws, out, (size_t)pl.dm.M * pl.dm.K, pl.t.c_split, bias, epi, pl.dm.P * pl.dm.Q,
+                                  pl.dm.Kb, st);
     return rc;
 }
 
@@ -210,25 +349,47 @@ extern "C" size_t ps_blocked_out_bytes(const ps_conv_desc *d)
     return (size_t)dm.M * dm.K * 4;
 }
 
-extern "C" int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
-                                  void *out_blk, void *stream)
+// Shared by the convolution entry points: validation, the cached pick when `t` is null (mode as in cached_pick), the
+// cached launch plan, the workspace check, the launch.
+static int conv_entry(const ps_conv_desc *d, const ps_tile *t, int mode, const void *in_blk, const void *wt_blk,
+                      void *out_blk, void *workspace, size_t workspace_bytes, void *stream, const float *bias, int epi)
 {
     Dims dm;
     int rc = make_dims(d, &dm);
     if (rc != PS_OK) return rc;
-    if (!t || !in_blk || !wt_blk || !out_blk) return PS_EINVAL;
-    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk)) return PS_EINVAL;
-    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, nullptr, (hipStream_t)stream);
+    if (!in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk) || !aligned16(workspace)) return PS_EINVAL;
+    ps_tile pick;
+    if (!t) {
+        rc = cached_pick(d, dm, mode, workspace ? workspace_bytes : 0, &pick);
+        if (rc != PS_OK) return rc;
+        t = &pick;
+    }
+    Plan storage;
+    const Plan *pl = nullptr;
+    rc = cached_plan(d, dm, *t, &storage, &pl);
+    if (rc != PS_OK) return rc;
+    const size_t need = mode ? pl->ws_need : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need)) return PS_EINVAL;
+    return run_plan(*pl, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr, (hipStream_t)stream, bias,
+                    epi);
+}
+
+extern "C" int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
+                                  void *out_blk, void *stream)
+{
+    if (!t) {
+        Dims dm;
+        const int rc = make_dims(d, &dm);
+        return rc != PS_OK ? rc : PS_EINVAL;
+    }
+    return conv_entry(d, t, 0, in_blk, wt_blk, out_blk, nullptr, 0, stream, nullptr, 0);
 }
 
 extern "C" int ps_conv2d_fwd(const ps_conv_desc *d, const void *in_blk, const void *wt_blk, void *out_blk,
                              void *stream)
 {
-    ps_tile t;
-    double us;
-    int rc = ps_tile_select(d, &t, &us);
-    if (rc != PS_OK) return rc;
-    return ps_conv2d_fwd_tile(d, &t, in_blk, wt_blk, out_blk, stream);
+    return conv_entry(d, nullptr, 0, in_blk, wt_blk, out_blk, nullptr, 0, stream, nullptr, 0);
 }
 
 extern "C" size_t ps_workspace_bytes(const ps_conv_desc *d, const ps_tile *t)
@@ -241,24 +402,7 @@ extern "C" size_t ps_workspace_bytes(const ps_conv_desc *d, const ps_tile *t)
 extern "C" int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
                                 void *out_blk, void *workspace, size_t workspace_bytes, void *stream)
 {
-    Dims dm;
-    int rc = make_dims(d, &dm);
-    if (rc != PS_OK) return rc;
-    if (!in_blk || !wt_blk || !out_blk) return PS_EINVAL;
-    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk) || !aligned16(workspace)) return PS_EINVAL;
-    ps_tile pick;
-    if (!t) {
-        double us;
-        rc = ps_tile_select_ws(d, workspace ? workspace_bytes : 0, &pick, &us);
-        if (rc != PS_OK) return rc;
-        t = &pick;
-    }
-    rc = tile_valid(dm, *t);
-    if (rc != PS_OK) return rc;
-    const size_t need = t->c_split > 1 ? (size_t)t->c_split * (size_t)dm.M * dm.K * 4 : 0;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return PS_EINVAL;
-    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr,
-                       (hipStream_t)stream);
+    return conv_entry(d, t, 1, in_blk, wt_blk, out_blk, workspace, workspace_bytes, stream, nullptr, 0);
 }
 
 extern "C" int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, const ps_epilogue *e, const void *in_blk,
@@ -268,26 +412,25 @@ extern "C" int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, cons
     Dims dm;
     int rc = make_dims(d, &dm);
     if (rc != PS_OK) return rc;
-    if (!e || !in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (!e) return PS_EINVAL;
     if (e->out_dtype != PS_F32 && e->out_dtype != PS_BF16) return PS_EUNSUPPORTED;
-    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk) || !aligned16(workspace) || !aligned16(e->bias))
-        return PS_EINVAL;
-    ps_tile pick;
-    if (!t) {
-        double us;
-        rc = ps_tile_select_ws(d, workspace ? workspace_bytes : 0, &pick, &us);
-        if (rc != PS_OK) return rc;
-        t = &pick;
-    }
-    rc = tile_valid(dm, *t);
-    if (rc != PS_OK) return rc;
-    // a split reduction can only apply the epilogue where the sum is complete: in the plane-adding pass
-    const size_t need = t->c_split > 1 ? (size_t)t->c_split * (size_t)dm.M * dm.K * 4 : 0;
-    if (need > 0 && (!workspace || workspace_bytes < need)) return PS_EINVAL;
+    if (!aligned16(e->bias)) return PS_EINVAL;
+    // a split reduction can only apply the epilogue where the sum is complete: in the plane-adding pass, so a split
+    // tile needs its workspace here (conv_entry refuses it without)
     const int epi = (e->bias ? 1 : 0) | (e->relu ? 2 : 0) | (e->out_dtype == PS_BF16 ? 4 : 0);
-    return conv_launch(dm, *t, in_blk, wt_blk, (float *)out_blk, need ? (float *)workspace : nullptr,
-                       (hipStream_t)stream, (const float *)e->bias, epi);
+    return conv_entry(d, t, 1, in_blk, wt_blk, out_blk, workspace, workspace_bytes, stream, (const float *)e->bias, epi);
 }
+
+extern "C" int ps_tile_pick(const ps_conv_desc *d, int with_workspace, size_t workspace_bytes, ps_tile *t)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!t) return PS_EINVAL;
+    return cached_pick(d, dm, with_workspace ? 1 : 0, with_workspace ? workspace_bytes : 0, t);
+}
+
+extern "C" size_t ps_tile_cache_entries(void) { return pick_cache().size() + plan_cache().size(); }
 
 extern "C" int ps_tile_kernel(const ps_conv_desc *d, const ps_tile *t)
 {

@@ -297,7 +297,8 @@ void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
     {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES, G,              \
      &launch_bf16<KT, MT, WK, WM, NBUF, G, 0>, &launch_bf16<KT, MT, WK, WM, NBUF, G, 1>,                 \
      &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, nullptr, halo_launch_or_null<KT, MT, WK, WM, NBUF>(),        \
-     halo_capacity_bytes<MT>()}
+     halo_capacity_bytes<MT>(), 0, Bf16Shape<KT, MT, WK, WM, NBUF, 3>::LDS_BYTES,                        \
+     halo_lds_bytes_or_zero<KT, MT, WK, WM, NBUF>()}
 #define PS_BF16_RINGS(KT, MT, WK, WM, G) PS_BF16_SHAPE(KT, MT, WK, WM, 2, G), PS_BF16_SHAPE(KT, MT, WK, WM, 4, G)
 
 //                 KT   MT  WK WM  G        wave tile (channels x pixels)

@@ -225,6 +225,14 @@ constexpr LaunchFn halo_launch_or_null()
     else
         return nullptr;
 }
+template <int KT, int MT, int WK, int WM, int NBUF>
+constexpr int halo_lds_bytes_or_zero()
+{
+    if constexpr (NBUF == 2 && 2 * ((MT >= 256 ? 20 : 14) * 1024 + (KT / 16) * 5120) <= 160 * 1024)
+        return HaloShape<KT, MT, WK, WM>::LDS_BYTES;
+    else
+        return 0;
+}
 template <int MT>
 constexpr int halo_capacity_bytes() { return (MT >= 256 ? 20 : 14) * 1024; }
 

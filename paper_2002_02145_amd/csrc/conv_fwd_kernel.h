@@ -591,6 +591,8 @@ struct ShapeEntry {
     LaunchFn launch_halo; // 3x3, stride 1, pad 1 with the input patch staged once per c-block (nullptr if none)
     int halo_bytes;       // capacity of that kernel's patch
     int stationary;       // 1: pixels with all their input channels stay in LDS (1x1 filters, C = 64 only)
+    int lds_3x3;          // LDS bytes of launch_3x3 / launch_halo where they differ from lds_bytes (0 = the same):
+    int lds_halo;         // the tile model prices occupancy with the footprint of the loop that will run
 };
 
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>

@@ -23,7 +23,7 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary, lds_3x3, lds_halo;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
 bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes);  // api.hip
@@ -127,7 +127,14 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double tiles_wave = (double)t.kt * t.mt / (waves_wg * 1024.0);  // 32x32 MFMA tiles per wave
     const double regs = 16.0 * tiles_wave + 2.0 * 8.0 * 2.0 * std::sqrt(tiles_wave) + 48.0;
     const double waves_simd = std::max(1.0, std::min(8.0, std::floor(c.regs_per_simd / regs)));
-    double occ = std::floor(c.lds_bytes / sh.lds_bytes);
+    // LDS footprint of the loop that will run: the 16-bit 3x3 loops (one filter row per ring slot, or the patch
+    // kernel's two c-block slots) differ from the general loop's
+    double lds_used = sh.lds_bytes;
+    if (patch && sh.lds_halo > 0)
+        lds_used = sh.lds_halo;
+    else if (dm.dtype != PS_F32 && baked && dm.R == 3 && sh.lds_3x3 > 0)
+        lds_used = sh.lds_3x3;
+    double occ = std::floor(c.lds_bytes / lds_used);
     occ = std::max(1.0, std::min(occ, std::floor(waves_simd * 4.0 / waves_wg)));
 
     // ---- matrix cores -----------------------------------------------------------------------------

@@ -135,3 +135,66 @@ def test_specialised_shapes_are_refused_where_they_do_not_apply(ps):
     d = ps.ConvDesc.of(S(2, 64, 8, 8, 256, 1, 1, 1, 0))
     assert ps.KERNEL_NAMES[ps.ps_tile_kernel(d, ps.Tile(*stationary))] == "1x1 pixel-stationary"
     assert ps.KERNEL_NAMES[ps.ps_tile_kernel(ps.ConvDesc.of(S(2, 3, 20, 20, 64, 7, 7, 2, 3)), ps.Tile(*n16))] == "7x7 tap-packed"
+
+
+def test_tile_cache_matches_uncached_selection_under_threads(ps):
+    """ps_tile_pick serves the convolution calls' tile from the per-process table; 8 threads asking for a mix of
+    descriptors, modes and workspace sizes at once must all see what the uncached ranking returns, and asking again
+    must add no entries."""
+    import threading
+    from shapes import EDGE_SHAPES
+    shapes = wl.resnet50_layers() + [wl.CFG1, wl.CFG3B] + EDGE_SHAPES
+    jobs = []
+    for s in shapes:
+        for dtype in (ps.PS_F32, ps.PS_BF16):
+            out_bytes = s.N * s.K * s.P * s.Q * 4
+            for with_ws, ws_bytes in ((0, 0), (1, 0), (1, 3 * out_bytes + 5), (1, 1 << 40)):
+                jobs.append((s, dtype, with_ws, ws_bytes))
+    expect = {}
+    for s, dtype, with_ws, ws_bytes in jobs:
+        d = ps.ConvDesc.of(s, dtype)
+        t = ps.ps_tile_select_ws(d, ws_bytes)[0] if with_ws else ps.ps_tile_select(d)[0]
+        expect[(s.name, dtype, with_ws, ws_bytes)] = t.as_tuple()
+    errors = []
+
+    def worker(k):
+        order = jobs[k::3] + jobs            # every thread starts elsewhere, then walks the whole list
+        for s, dtype, with_ws, ws_bytes in order:
+            got = ps.ps_tile_pick(ps.ConvDesc.of(s, dtype), with_ws, ws_bytes).as_tuple()
+            if got != expect[(s.name, dtype, with_ws, ws_bytes)]:
+                errors.append((s.name, dtype, with_ws, ws_bytes, got))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(8)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors[:3]
+    filled = ps.ps_tile_cache_entries()
+    assert 0 < filled <= len(jobs)
+    worker(0)
+    assert ps.ps_tile_cache_entries() == filled
+    # workspace sizes that admit the same number of partial planes share an entry
+    d = ps.ConvDesc.of(wl.CFG1)
+    out_bytes = wl.CFG1.N * wl.CFG1.K * wl.CFG1.P * wl.CFG1.Q * 4
+    ps.ps_tile_pick(d, 1, 9 * out_bytes)
+    n = ps.ps_tile_cache_entries()
+    assert ps.ps_tile_pick(d, 1, 9 * out_bytes + 100).as_tuple() == ps.ps_tile_select_ws(d, 9 * out_bytes + 100)[0].as_tuple()
+    assert ps.ps_tile_cache_entries() == n
+    with pytest.raises(ps.PsError):
+        ps.ps_tile_pick(ps.ConvDesc.of(wl.ConvShape(1, 16, 8, 8, 24, 3, 3, 1, 1)))
+
+
+def test_steady_state_pick_is_a_lookup(ps):
+    """After the first call the pick costs a table lookup: far below the microseconds the ranking itself takes."""
+    import time
+    worst = 0.0
+    for s in wl.resnet50_layers():
+        for dtype in (ps.PS_F32, ps.PS_BF16):
+            d = ps.ConvDesc.of(s, dtype)
+            ps.ps_tile_pick(d, 1, 256 << 20)
+            t0 = time.perf_counter()
+            for _ in range(2000):
+                ps.lib.ps_tile_pick(ctypes.byref(d), 1, 256 << 20, ctypes.byref(ps.Tile()))
+            worst = max(worst, (time.perf_counter() - t0) / 2000)
+    assert worst < 5e-6, f"steady pick costs {worst * 1e6:.2f} us per call (ctypes overhead included)"
