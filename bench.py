@@ -8,11 +8,13 @@ network input / per layer; their bandwidth is reported beside the headline, not 
 
 Prints ONE JSON line.  Extra keys: ``roofline`` (dominant kernel against the fp32 MFMA peak, timed
 with HIP events on the launch stream), ``cpu_baseline`` (the CPU oracle on the host cores),
-``layers`` (every ResNet-50-shaped layer with the tile model's pick), ``transforms``.
+``layers`` (every ResNet-50-shaped layer with the tile model's pick), ``transforms``, ``bf16`` (the same layers with
+bf16 inputs), ``via_select`` and ``api_call_host_us`` (the call that picks its own tile against an explicit tile).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import math
 import os
@@ -26,6 +28,38 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
+
+
+def kernel_source_digest(dtype: str) -> str:
+    """Digest of the kernel sources of `dtype`: the stored HBM-traffic counters only describe the kernel they were
+    taken on."""
+    h = hashlib.sha256()
+    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip"] + (["conv_fwd_bf16_halo.h"] if dtype == "bf16" else
+                                                            ["conv_fwd_f32_n16.h", "conv_fwd_f32_n16_kloop.h"])
+    for f in files:
+        with open(os.path.join(ROOT, "paper_2002_02145_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def _precondition(fn, min_ms: float = 80.0) -> float:
+    """Runs fn() back to back for at least min_ms of GPU time and returns the milliseconds spent.  The shader clock
+    needs tens of milliseconds of load to settle at the level it sustains; launches timed before that read 10-15 %
+    slower than the same kernel in steady state, whatever the counted warm-up is."""
+    import torch
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    spent, chunk = 0.0, 50
+    while spent < min_ms:
+        for _ in range(chunk):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        spent = e0.elapsed_time(e1)
+        chunk = min(2000, chunk * 2)
+    return spent
 
 
 def _time_steps(fn, steps: int, warmup: int):
@@ -71,14 +105,110 @@ MEASURED_TRAFFIC = {"f32": ("c63efe339e07e77e", (64, 176, 2, 1, 0), 3, 46600669)
                     "bf16": ("6a25d7e77a9480b1", (64, 256, 2, 1, 0), 9, 34618179)}
 
 
+def _layer_rows(ps, wl, torch, dtype_name: str, workspace, ws_cap: int):
+    """Every ResNet-50-shaped layer with the library's own pick: microseconds, TFLOP/s, fractions of the MFMA peak
+    and of min(MFMA, HBM).  Device-side random tensors (timing only)."""
+    dtype = ps.PS_F32 if dtype_name == "f32" else ps.PS_BF16
+    tdt = torch.float32 if dtype_name == "f32" else torch.bfloat16
+    es = 4 if dtype_name == "f32" else 2
+    dev = "cuda:0"
+    g = torch.Generator(device=dev).manual_seed(7)
+    rows = []
+    base = wl.resnet50_layers()
+    for L in base + [wl.CFG3B]:
+        dl = ps.ConvDesc.of(L, dtype)
+        xi = torch.rand(ps.ps_blocked_in_bytes(dl) // es, device=dev, generator=g).to(tdt)
+        wi = ((torch.rand(ps.ps_blocked_wt_bytes(dl) // es, device=dev, generator=g) - 0.5) * 0.1).to(tdt)
+        oi = torch.empty(ps.ps_blocked_out_bytes(dl) // 4, device=dev, dtype=torch.float32)
+        t = ps.ps_tile_pick(dl, True, ws_cap)
+        fn = lambda: ps.ps_conv2d_fwd_ws(dl, None, xi, wi, oi, workspace, ws_cap)   # the library picks (cached)
+        _precondition(fn, 60.0)
+        reps = max(200, min(3000, int(120e-3 / (L.flops / (PEAK_TFLOPS[dtype_name] * 1e12 * 0.3) + 8e-6))))
+        _, ms = _time_steps(fn, reps, 20)
+        tf = L.flops / (ms * 1e-3) * 1e-12
+        t_roof = max(L.flops / (PEAK_TFLOPS[dtype_name] * 1e12), L.algorithmic_bytes(es) / (HBM_PEAK_GBS * 1e9))
+        rows.append({"layer": L.name, "us": round(ms * 1e3, 2), "TFLOP/s": round(tf, 2),
+                     "frac_mfma_peak": round(tf / PEAK_TFLOPS[dtype_name], 4),
+                     "frac_min_mfma_hbm_roofline": round(t_roof / (ms * 1e-3), 4),
+                     "tile": list(t.as_tuple()), "kernel": ps.KERNEL_NAMES[ps.ps_tile_kernel(dl, t)]})
+        del xi, wi, oi
+    n = len(base)
+    tot_flop = sum(L.flops for L in base)
+    tot_s = sum(r["us"] for r in rows[:n]) * 1e-6
+    agg = {"flop_weighted_TFLOP/s": round(tot_flop / tot_s * 1e-12, 2),
+           "geomean_TFLOP/s": round(math.exp(sum(math.log(r["TFLOP/s"]) for r in rows[:n - 1]) / (n - 1)), 2),
+           "geomean_covers": "the 12 layers whose channel counts are multiples of 16 (the paper's selection, Section 5.1)"}
+    return rows, agg
+
+
+class _Headline:
+    """Blocked tensors of one seeded layer resident on the device, and the calls that are timed on them."""
+
+    def __init__(self, ps, wl, torch, shape, dtype_name: str, workspace, ws_cap: int):
+        self.ps, self.shape, self.dtype_name = ps, shape, dtype_name
+        dev = "cuda:0"
+        self.dtype = ps.PS_F32 if dtype_name == "f32" else ps.PS_BF16
+        self.tdt = torch.float32 if dtype_name == "f32" else torch.bfloat16
+        self.es = 4 if dtype_name == "f32" else 2
+        x, w = wl.relu_like(shape, 2)
+        if dtype_name == "bf16":
+            x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
+        self.x, self.w = x, w
+        d = self.d = ps.ConvDesc.of(shape, self.dtype)
+        self.xd = torch.from_numpy(x).to(self.tdt).to(dev)
+        self.wd = torch.from_numpy(w).to(self.tdt).to(dev)
+        self.xb = torch.empty(ps.ps_blocked_in_bytes(d) // self.es, dtype=self.tdt, device=dev)
+        self.wb = torch.empty(ps.ps_blocked_wt_bytes(d) // self.es, dtype=self.tdt, device=dev)
+        self.ob = torch.empty(ps.ps_blocked_out_bytes(d) // 4, dtype=torch.float32, device=dev)
+        self.y = torch.empty((shape.N, shape.K, shape.P, shape.Q), dtype=torch.float32, device=dev)
+        ps.ps_nchw_to_blocked(d, self.xd, self.xb)
+        ps.ps_kcrs_to_blocked(d, self.wd, self.wb)
+        # ranking cost, first and steady (host only; the first call prices every candidate, later ones are lookups)
+        t0 = time.perf_counter()
+        self.tile = ps.ps_tile_pick(d, True, ws_cap)
+        t1 = time.perf_counter()
+        for _ in range(1000):
+            ps.ps_tile_pick(d, True, ws_cap)
+        t2 = time.perf_counter()
+        self.pick_first_us, self.pick_steady_us = (t1 - t0) * 1e6, (t2 - t1) / 1000 * 1e6
+        _, self.model_us = ps.ps_tile_select_ws(d, ws_cap)
+        self.ws_bytes = ps.ps_workspace_bytes(d, self.tile)
+        self.ws = workspace
+        # the timed step: explicit tile (what the sweeps time); and the same launch with the library choosing
+        self.step = lambda: ps.ps_conv2d_fwd_ws(d, self.tile, self.xb, self.wb, self.ob, self.ws, self.ws_bytes)
+        self.step_select = lambda: ps.ps_conv2d_fwd_ws(d, None, self.xb, self.wb, self.ob, self.ws, ws_cap)
+
+    def host_call_us(self, fn, calls: int = 300) -> float:
+        """Host time of one call (argument marshalling, pick and plan lookup, kernel launch), queue not full."""
+        import torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(calls):
+            fn()
+        dt = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        return dt / calls * 1e6
+
+    def check(self, oracle):
+        import torch
+        ps = self.ps
+        ps.ps_blocked_to_nkpq(self.d, self.ob, self.y)
+        torch.cuda.synchronize()
+        got = self.y.cpu().numpy()
+        out, mag = oracle.conv2d_fwd(self.shape, self.x, self.w)
+        err = oracle.normalised_error(got, out, mag)
+        tol = 1e-4 if self.dtype_name == "f32" else 2e-2
+        return {"max_normalised_error": err, "tolerance": tol, "pass": bool(err <= tol)}
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3000)
-    ap.add_argument("--warmup", type=int, default=1000,
-                    help="untimed steps first; the GPU needs tens of milliseconds of load to reach its sustained clocks")
+    ap.add_argument("--warmup", type=int, default=1000, help="untimed steps before the timed ones")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--no-layers", action="store_true", help="skip the per-layer sweep")
+    ap.add_argument("--no-layers", action="store_true", help="skip the per-layer sweeps")
+    ap.add_argument("--no-bf16", action="store_true", help="skip the bf16 section of an fp32 run")
     ap.add_argument("--layer", default=None,
                     help="time this layer of the ResNet-50-shaped sweep instead of the headline one (for profiling a "
                          "kernel the headline does not use; the default run is the benchmark)")
@@ -101,8 +231,6 @@ def main(argv=None) -> int:
         return 2
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    dtype = ps.PS_F32 if a.dtype == "f32" else ps.PS_BF16
-    tdt = torch.float32 if a.dtype == "f32" else torch.bfloat16
     es = 4 if a.dtype == "f32" else 2
 
     # ---- headline workload: ResNet-50-shaped 3x3, N=28, C=K=64, 56x56 -------------------------
@@ -113,26 +241,21 @@ def main(argv=None) -> int:
             print(f"bench.py: unknown layer {a.layer}; one of {sorted(named)}", file=sys.stderr)
             return 2
         shape = named[a.layer]
-    x, w = wl.relu_like(shape, 2)
-    if a.dtype == "bf16":
-        x, w = wl.round_to_bf16(x), wl.round_to_bf16(w)
-    d = ps.ConvDesc.of(shape, dtype)
-    xd = torch.from_numpy(x).to(tdt).to(dev)
-    wd = torch.from_numpy(w).to(tdt).to(dev)
-    xb = torch.empty(ps.ps_blocked_in_bytes(d) // es, dtype=tdt, device=dev)
-    wb = torch.empty(ps.ps_blocked_wt_bytes(d) // es, dtype=tdt, device=dev)
-    ob = torch.empty(ps.ps_blocked_out_bytes(d) // 4, dtype=torch.float32, device=dev)
-    y = torch.empty((shape.N, shape.K, shape.P, shape.Q), dtype=torch.float32, device=dev)
-    ps.ps_nchw_to_blocked(d, xd, xb)
-    ps.ps_kcrs_to_blocked(d, wd, wb)
     WS_CAP = 256 << 20   # workspace the caller is willing to lend for split reductions
-    tile, model_us = ps.ps_tile_select_ws(d, WS_CAP)
-    ws_bytes = ps.ps_workspace_bytes(d, tile)
-    ws = torch.empty(max(ws_bytes, 16) // 4, dtype=torch.float32, device=dev)
-    step = lambda: ps.ps_conv2d_fwd_ws(d, tile, xb, wb, ob, ws, ws_bytes)
+    workspace = torch.empty(WS_CAP // 4, dtype=torch.float32, device=dev)
+    hl = _Headline(ps, wl, torch, shape, a.dtype, workspace, WS_CAP)
+    d, tile, step = hl.d, hl.tile, hl.step
+    xb, wb, ob, y, xd, wd, ws, ws_bytes = hl.xb, hl.wb, hl.ob, hl.y, hl.xd, hl.wd, hl.ws, hl.ws_bytes
 
+    # the clocks settle under load first (time-based, not counted in --warmup), then W untimed and K timed steps
+    precond_ms = _precondition(step)
     wall_ms, ev_ms = _time_steps(step, a.steps, a.warmup)
     gflops = shape.flops / (wall_ms * 1e-3) * 1e-9
+    # the same launch when the library picks the tile itself (cached ranking): must cost the same
+    _, sel_ms = _time_steps(hl.step_select, max(a.steps, 200), max(a.warmup, 20))
+    _, exp_ms = _time_steps(step, max(a.steps, 200), max(a.warmup, 20))
+    host_select_us = hl.host_call_us(hl.step_select)
+    host_explicit_us = hl.host_call_us(step)
     each_ms = _time_each(step, min(500, max(20, a.steps)))
     # cold regime: rotate through enough distinct input/output pairs (> 512 MB) that no launch finds its
     # tensors in the Infinity Cache
@@ -151,7 +274,6 @@ def main(argv=None) -> int:
     # events around the timed region give it directly (this is what a kernel trace averages to); a split tile
     # adds the plane-adding pass to every step, and its time is charged to the convolution kernel as well
     kernel_ms = ev_ms
-    from paper_2002_02145_amd.profile_summary import kernel_source_digest
     digest, ttile, tvariant, tbytes = MEASURED_TRAFFIC.get(a.dtype, (None, None, None, None))
     same_launch = (a.layer is None and digest == kernel_source_digest(a.dtype) and ttile == tile.as_tuple()
                    and tvariant == ps.ps_tile_kernel(d, tile))
@@ -177,56 +299,46 @@ def main(argv=None) -> int:
         del src, dst
 
     # ---- correctness of what was timed, and the CPU baseline, on the same inputs ----------------
-    ps.ps_blocked_to_nkpq(d, ob, y)
-    torch.cuda.synchronize()
-    got = y.cpu().numpy()
     cpu = None
     checked = None
+    oracle = None
     if not a.no_cpu_baseline:
         import oracle
         oracle.build()
+        step()
+        checked = hl.check(oracle)
         reps, t0 = 0, time.perf_counter()
         while True:
-            out, mag = oracle.conv2d_fwd(shape, x, w)
+            oracle.conv2d_fwd(shape, hl.x, hl.w)
             reps += 1
             if time.perf_counter() - t0 >= 8.0 or reps >= 200:
                 break
         dt = (time.perf_counter() - t0) / reps
-        err = oracle.normalised_error(got, out, mag)
-        tol = 1e-4 if a.dtype == "f32" else 2e-2
-        checked = {"max_normalised_error": err, "tolerance": tol, "pass": bool(err <= tol)}
         cpu = {"value": round(shape.flops / dt * 1e-9, 3), "unit": "GFLOP/s", "cores": oracle.threads(),
                "kind": "oracle", "sample": f"whole layer {shape.name} (all {shape.N} images), {reps} repetitions of "
                                           f"{dt:.2f} s each; fp64 seven-loop definition, OpenMP over (n, k)"}
 
     # ---- every ResNet-50-shaped layer with the model's pick --------------------------------------
-    layers = []
-    if not a.no_layers:
-        g = torch.Generator(device=dev).manual_seed(7)
-        for L in wl.resnet50_layers() + [wl.CFG3B]:
-            dl = ps.ConvDesc.of(L, dtype)
-            xi = torch.rand(ps.ps_blocked_in_bytes(dl) // es, device=dev, generator=g).to(tdt)
-            wi = ((torch.rand(ps.ps_blocked_wt_bytes(dl) // es, device=dev, generator=g) - 0.5) * 0.1).to(tdt)
-            oi = torch.empty(ps.ps_blocked_out_bytes(dl) // 4, device=dev, dtype=torch.float32)
-            t, _ = ps.ps_tile_select_ws(dl, WS_CAP)
-            wsb = ps.ps_workspace_bytes(dl, t)
-            wsl = torch.empty(max(wsb, 16) // 4, dtype=torch.float32, device=dev)
-            # enough launches to hold the clocks at their sustained level: ~60 ms of warm-up, twice that timed
-            reps = max(200, min(3000, int(60e-3 / (L.flops / (PEAK_TFLOPS[a.dtype] * 1e12 * 0.3) + 8e-6))))
-            _, ms = _time_steps(lambda: ps.ps_conv2d_fwd_ws(dl, t, xi, wi, oi, wsl, wsb), 2 * reps, reps)
-            tf = L.flops / (ms * 1e-3) * 1e-12
-            t_roof = max(L.flops / (PEAK_TFLOPS[a.dtype] * 1e12), L.algorithmic_bytes(es) / (HBM_PEAK_GBS * 1e9))
-            layers.append({"layer": L.name, "us": round(ms * 1e3, 2), "TFLOP/s": round(tf, 2),
-                           "frac_mfma_peak": round(tf / PEAK_TFLOPS[a.dtype], 4),
-                           "frac_min_mfma_hbm_roofline": round(t_roof / (ms * 1e-3), 4),
-                           "tile": list(t.as_tuple())})
-            del xi, wi, oi, wsl
-        tot_flop = sum(L.flops for L in wl.resnet50_layers())
-        tot_s = sum(l["us"] for l in layers[:len(wl.resnet50_layers())]) * 1e-6
-        agg = {"flop_weighted_TFLOP/s": round(tot_flop / tot_s * 1e-12, 2),
-               "geomean_TFLOP/s": round(math.exp(sum(math.log(l["TFLOP/s"]) for l in layers[:13]) / 13), 2)}
-    else:
-        agg = None
+    layers, agg = ([], None) if a.no_layers else _layer_rows(ps, wl, torch, a.dtype, workspace, WS_CAP)
+
+    # ---- the 16-bit configuration (same layers, bf16 inputs and filters, fp32 accumulation and output) -------
+    bf16 = None
+    if a.dtype == "f32" and not a.no_bf16 and a.layer is None:
+        hb = _Headline(ps, wl, torch, wl.CFG2, "bf16", workspace, WS_CAP)
+        _precondition(hb.step)
+        _, b_ms = _time_steps(hb.step, max(a.steps, 1000), max(a.warmup, 100))
+        b_alg = wl.CFG2.algorithmic_bytes(2)
+        b_tf = wl.CFG2.flops / (b_ms * 1e-3) * 1e-12
+        bf16 = {"workload": "same layer, inputs and filters rounded to bf16 (nearest even), fp32 accumulate and output",
+                "us": round(b_ms * 1e3, 2), "TFLOP/s": round(b_tf, 1), "frac_mfma_peak": round(b_tf / PEAK_TFLOPS["bf16"], 4),
+                "roofline": {"bound": "hbm", "achieved": round(b_alg / (b_ms * 1e-3) * 1e-9, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(b_alg / (b_ms * 1e-3) * 1e-9 / HBM_PEAK_GBS, 4),
+                             "algorithmic_bytes": b_alg},
+                "tile": list(hb.tile.as_tuple()), "kernel": ps.KERNEL_NAMES[ps.ps_tile_kernel(hb.d, hb.tile)],
+                "checked_against_oracle": hb.check(oracle) if oracle is not None else None}
+        if not a.no_layers:
+            bf16["layers"], bf16["layers_aggregate"] = _layer_rows(ps, wl, torch, "bf16", workspace, WS_CAP)
+        del hb
 
     peak = PEAK_TFLOPS[a.dtype]
     alg_bytes = shape.algorithmic_bytes(es)
@@ -247,12 +359,12 @@ def main(argv=None) -> int:
     sink = torch.zeros(1024, dtype=torch.float32, device=dev)
     probe_iters = 2000 if a.dtype == "f32" else 4000
     for _ in range(3):
-        probe_flop = ps.ps_probe_mfma(dtype, probe_iters, sink)
+        probe_flop = ps.ps_probe_mfma(hl.dtype, probe_iters, sink)
     torch.cuda.synchronize()
     pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     pe0.record(torch.cuda.current_stream())
     for _ in range(10):
-        ps.ps_probe_mfma(dtype, probe_iters, sink)
+        ps.ps_probe_mfma(hl.dtype, probe_iters, sink)
     pe1.record(torch.cuda.current_stream())
     torch.cuda.synchronize()
     probe_tflops = probe_flop * 10 / (pe0.elapsed_time(pe1) * 1e-3) * 1e-12
@@ -272,8 +384,18 @@ def main(argv=None) -> int:
         "config": {"workload": f"ResNet-50-shaped {shape.R}x{shape.S} conv fwd ({shape.name}): N={shape.N} C={shape.C} "
                                f"K={shape.K} H=W={shape.H} R=S={shape.R} stride {shape.stride} pad {shape.pad}, "
                                f"blocked 16c layouts, tensors resident in HBM",
-                   "tile": list(tile.as_tuple()), "tile_model_us": round(model_us, 2),
+                   "tile": list(tile.as_tuple()), "tile_model_us": round(hl.model_us, 2),
                    "timing": "warm (same buffers every step)"},
+        "preconditioning_ms": round(precond_ms, 1),
+        "via_select": {"us": round(sel_ms * 1e3, 2), "explicit_tile_us": round(exp_ms * 1e3, 2),
+                       "ratio": round(sel_ms / exp_ms, 4),
+                       "what": "ps_conv2d_fwd_ws with tile = NULL (library picks, cached) against the same launch with "
+                               "the tile passed in"},
+        "api_call_host_us": {"pick_first": round(hl.pick_first_us, 2), "pick_steady": round(hl.pick_steady_us, 2),
+                             "call_with_select": round(host_select_us, 2), "call_with_explicit_tile": round(host_explicit_us, 2),
+                             "what": "host time through the Python binding: ps_tile_pick alone (first call ranks every "
+                                     "candidate, later calls are lookups), and one whole ps_conv2d_fwd_ws call "
+                                     "including the kernel launch"},
         "cold": {"us": round(cold_ms * 1e3, 2), "GFLOP/s": round(shape.flops / (cold_ms * 1e-3) * 1e-9, 1),
                  "buffer_sets": n_sets, "bytes_rotated": n_sets * pair_bytes},
         "frac_mfma_peak": round(gflops * 1e-3 / peak, 4),
@@ -285,6 +407,7 @@ def main(argv=None) -> int:
         "with_layout_transforms_GFLOP/s": round(shape.flops / (e2e_ms * 1e-3) * 1e-9, 1),
         "layers": layers,
         "layers_aggregate": agg,
+        "bf16": bf16,
         "paper_context": "paper: 2448 GFLOP/s geomean on ResNet-50 layers, 28-core Xeon 8280, fp32 (Table 1)",
     }
     print(json.dumps(line))

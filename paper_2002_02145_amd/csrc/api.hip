@@ -22,6 +22,12 @@ int make_dims(const ps_conv_desc *d, Dims *o)
     const long long hp = (long long)d->H + 2LL * d->pad - d->R, wp = (long long)d->W + 2LL * d->pad - d->S;
     if (hp < 0 || wp < 0) return PS_EINVAL;
     if (d->K % kBlock != 0) return PS_EUNSUPPORTED;
+    // No field of a tensor that stays below 2 GiB can reach 2^27, and strides or pads beyond 2^20 have no use: refusing
+    // them here keeps every later product inside 64 bits (and the sums above inside 32).
+    const int32_t big = 1 << 27;
+    if (d->N > big || d->C > big || d->H > big || d->W > big || d->K > big || d->R > big || d->S > big ||
+        d->stride > (1 << 20) || d->pad > (1 << 20))
+        return PS_EUNSUPPORTED;
     o->N = d->N; o->C = d->C; o->H = d->H; o->W = d->W; o->K = d->K; o->R = d->R; o->S = d->S;
     o->stride = d->stride; o->pad = d->pad; o->dtype = d->dtype;
     o->es = d->dtype == PS_F32 ? 4 : 2;
@@ -29,14 +35,17 @@ int make_dims(const ps_conv_desc *d, Dims *o)
     o->Q = (int)(wp / d->stride) + 1;
     o->Cb = (d->C + kBlock - 1) / kBlock;
     o->Kb = d->K / kBlock;
+    // 32-bit byte offsets inside the kernels: every blocked tensor must stay below 2 GiB (sizes compared as doubles:
+    // four factors of up to 2^27 do not fit 64-bit integers, and the comparison needs no exactness at that size)
+    const double lim = 2147483647.0;
+    const double nb_d = (double)o->Cb * d->R * d->S;
+    const double m_d = (double)d->N * o->P * o->Q;
+    const double in_b = (double)d->N * o->Cb * d->H * d->W * kBlock * o->es;
+    const double wt_b = (double)o->Kb * nb_d * kBlock * kBlock * o->es;
+    const double out_b = m_d * d->K * 4;
+    if (nb_d > (double)(1 << 24) || in_b > lim || wt_b > lim || out_b > lim) return PS_EUNSUPPORTED;
     const long long nb = (long long)o->Cb * d->R * d->S;
     o->M = (long long)d->N * o->P * o->Q;
-    // 32-bit byte offsets inside the kernels: every blocked tensor must stay below 2 GiB
-    const long long lim = (1LL << 31) - 1;
-    const long long in_b = (long long)d->N * o->Cb * d->H * d->W * kBlock * o->es;
-    const long long wt_b = (long long)o->Kb * nb * kBlock * kBlock * o->es;
-    const long long out_b = o->M * d->K * 4;
-    if (nb > (1 << 24) || in_b > lim || wt_b > lim || out_b > lim) return PS_EUNSUPPORTED;
     o->NB = (int)nb;
     return PS_OK;
 }

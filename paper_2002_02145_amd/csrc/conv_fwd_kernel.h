@@ -137,14 +137,16 @@ __device__ inline void wait_vm_and_barrier()
 
 typedef unsigned uintx2_t __attribute__((ext_vector_type(2)));
 
-// Two finite fp32 values rounded to bf16 (nearest, ties to even), packed low | high << 16.
-__device__ inline unsigned pack_bf16(float lo, float hi)
+// Two fp32 values rounded to bf16 (nearest, ties to even), packed low | high << 16.  A NaN keeps its sign and the
+// upper payload bits and gets the quiet bit (the rounding add would otherwise carry a NaN whose only set mantissa
+// bits are low ones into the exponent: infinity).
+__device__ inline unsigned bf16_bits_rne(float x)
 {
-    const unsigned a = __builtin_bit_cast(unsigned, lo), b = __builtin_bit_cast(unsigned, hi);
-    const unsigned ra = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
-    const unsigned rb = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
-    return ra | rb;
+    const unsigned a = __builtin_bit_cast(unsigned, x);
+    const unsigned r = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
+    return (a & 0x7FFFFFFFu) > 0x7F800000u ? (a >> 16) | 0x40u : r;
 }
+__device__ inline unsigned pack_bf16(float lo, float hi) { return bf16_bits_rne(lo) | (bf16_bits_rne(hi) << 16); }
 
 // Epilogue shared by the fp32 and bf16 kernels: accumulators -> out[n][kb][p][q][16 k].
 // acc[tk][tm] is the 32x32 tile (output channels x pixels) number (tk, tm) of this wave in the MFMA

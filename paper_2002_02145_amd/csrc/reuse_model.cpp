@@ -171,6 +171,8 @@ extern "C" int ps_reuse_assign(const int64_t *ws, int n_ws, const int64_t *cache
 {
     if (n_ws < 0 || (n_ws > 0 && !ws) || n_levels < 0 || (n_levels > 0 && (!cache_sizes || !level_ws)) || !mem_ws)
         return PS_EINVAL;
+    for (int i = 0; i < n_levels; ++i)
+        if (cache_sizes[i] < 0) return PS_EINVAL;
     std::vector<int64_t> s(ws, ws + n_ws);
     for (int64_t w : s)
         if (w < 0) return PS_EINVAL;
@@ -180,9 +182,9 @@ extern "C" int ps_reuse_assign(const int64_t *ws, int n_ws, const int64_t *cache
     *mem_ws = 0;
     for (int64_t w : s) {
         int i = 0;
-        while (i < n_levels && w + level_ws[i] > cache_sizes[i]) ++i;
+        while (i < n_levels && w > cache_sizes[i] - level_ws[i]) ++i;  // (level_ws[i] <= cache_sizes[i]: no overflow)
         if (i < n_levels) level_ws[i] += w;
-        else *mem_ws += w;
+        else *mem_ws = w > INT64_MAX - *mem_ws ? INT64_MAX : *mem_ws + w;
     }
     return PS_OK;
 }
