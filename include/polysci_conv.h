@@ -43,7 +43,8 @@ typedef enum {
     PS_EINVAL = -1,       /* null pointer, non-positive size, P or Q <= 0, misaligned pointer */
     PS_EUNSUPPORTED = -2, /* K % 16 != 0, unknown dtype, tensor too large for 32-bit element offsets,
                              tile not valid for this descriptor */
-    PS_EHIP = -3          /* the HIP runtime reported an error at launch */
+    PS_EHIP = -3,         /* the HIP runtime reported an error at launch */
+    PS_ESCRATCH = -4      /* ps_conv2d_fwd_static: the tile needs more scratch than PS_STATIC_SCRATCH_BYTES */
 } ps_status;
 
 typedef enum { PS_F32 = 0, PS_BF16 = 1 } ps_dtype; /* element type of input and filter */
@@ -111,6 +112,22 @@ int ps_conv2d_fwd_tile(const ps_conv_desc *d, const ps_tile *t, const void *in_b
 size_t ps_workspace_bytes(const ps_conv_desc *d, const ps_tile *t); /* c_split * N*K*P*Q*4, 0 if c_split == 1 */
 int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
                      void *out_blk, void *workspace, size_t workspace_bytes, void *stream);
+
+/* For callers that cannot allocate device memory and have no workspace to lend (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): ps_conv2d_fwd_ws with the workspace replaced by an array the
+ * library holds in static device memory, PS_STATIC_SCRATCH_BYTES (64 MiB) per GPU, there until the process ends.
+ * The call allocates and frees nothing on the device and calls no allocating runtime routine; the caller passes only
+ * inputs and outputs.  t == NULL runs the pick among the tiles whose partial planes fit the array (ps_tile_pick with
+ * workspace_bytes = PS_STATIC_SCRATCH_BYTES); an explicit tile whose planes need more (ps_workspace_bytes) returns
+ * PS_ESCRATCH and launches nothing.  Results are those of ps_conv2d_fwd_ws with the same tile, bit for bit.
+ * The array keeps the last call's contents; nothing in it has to start at zero (every plane element that is read
+ * was stored by the same call), so nothing is cleared.  All calls on one GPU share that GPU's array: calls that can
+ * overlap in time on one GPU (different streams, different threads) race on it and must be ordered by the caller.
+ * The array's device address is looked up on the first call on each device (one symbol query, kept afterwards);
+ * make that first call outside stream capture. */
+#define PS_STATIC_SCRATCH_BYTES (64u << 20)
+int ps_conv2d_fwd_static(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
+                         void *out_blk, void *stream);
 
 /* Convolution with the work of the following layers of an inference pipeline fused into the store of the output
  * tile (Section 5 evaluates the convolutions of such pipelines; what follows each one there is a bias, an activation

@@ -13,7 +13,8 @@ from dataclasses import dataclass
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpsconv.so")
 
-PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP = 0, -1, -2, -3
+PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EHIP, PS_ESCRATCH = 0, -1, -2, -3, -4
+PS_STATIC_SCRATCH_BYTES = 64 << 20
 PS_F32, PS_BF16 = 0, 1
 
 
@@ -104,6 +105,7 @@ def _load() -> ctypes.CDLL:
         "ps_conv2d_fwd_tile": (ctypes.c_int, [dp, tp, vp, vp, vp, vp]),
         "ps_workspace_bytes": (ctypes.c_size_t, [dp, tp]),
         "ps_conv2d_fwd_ws": (ctypes.c_int, [dp, tp, vp, vp, vp, vp, ctypes.c_size_t, vp]),
+        "ps_conv2d_fwd_static": (ctypes.c_int, [dp, tp, vp, vp, vp, vp]),
         "ps_conv2d_fwd_fused": (ctypes.c_int, [dp, tp, ctypes.POINTER(Epilogue), vp, vp, vp, vp, ctypes.c_size_t, vp]),
         "ps_tile_kernel": (ctypes.c_int, [dp, tp]),
         "ps_tile_pick": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_size_t, tp]),
@@ -224,6 +226,13 @@ def ps_conv2d_fwd_ws(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace, w
     tp = ctypes.byref(tile) if tile is not None else None
     _check(lib.ps_conv2d_fwd_ws(ctypes.byref(desc), tp, _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk),
                                 _ptr(workspace), int(workspace_bytes), _stream(stream)), "ps_conv2d_fwd_ws")
+
+
+def ps_conv2d_fwd_static(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, stream=None) -> None:
+    """ps_conv2d_fwd_ws on the library's static scratch array (no allocation anywhere); tile=None lets it pick."""
+    tp = ctypes.byref(tile) if tile is not None else None
+    _check(lib.ps_conv2d_fwd_static(ctypes.byref(desc), tp, _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk),
+                                    _stream(stream)), "ps_conv2d_fwd_static")
 
 
 def ps_conv2d_fwd_fused(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace=None, workspace_bytes: int = 0,

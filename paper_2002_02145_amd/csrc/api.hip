@@ -1,5 +1,6 @@
 // C ABI entry points: descriptor validation, size queries, convolution launch.
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <shared_mutex>
@@ -414,6 +415,56 @@ extern "C" int ps_conv2d_fwd_ws(const ps_conv_desc *d, const ps_tile *t, const v
     return conv_entry(d, t, 1, in_blk, wt_blk, out_blk, workspace, workspace_bytes, stream, nullptr, 0);
 }
 
+// ---- library-owned scratch for callers that cannot allocate ---------------------------------------------------
+// One array per GPU (every device that loads this code object holds its own copy at its own address, until the
+// process ends).  In host code the array's name is only a handle for the symbol lookup: the address a kernel can use
+// is what hipGetSymbolAddress returns with that device current, looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[PS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_status(e);
+    if (dev < 0 || dev >= kMaxDevices) return PS_EUNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return hip_status(e != hipSuccess ? e : hipErrorInvalidSymbol);
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return PS_OK;
+}
+}  // namespace
+
+extern "C" int ps_conv2d_fwd_static(const ps_conv_desc *d, const ps_tile *t, const void *in_blk, const void *wt_blk,
+                                    void *out_blk, void *stream)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (!in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (t) {  // an explicit tile whose partial planes exceed the array is refused before anything is looked up
+        rc = tile_valid(dm, *t);
+        if (rc != PS_OK) return rc;
+        if (t->c_split > 1 && (size_t)t->c_split * (size_t)dm.M * dm.K * 4 > (size_t)PS_STATIC_SCRATCH_BYTES) return PS_ESCRATCH;
+    }
+    void *ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != PS_OK) return rc;
+    return conv_entry(d, t, 1, in_blk, wt_blk, out_blk, ws, (size_t)PS_STATIC_SCRATCH_BYTES, stream, nullptr, 0);
+}
+
 extern "C" int ps_conv2d_fwd_fused(const ps_conv_desc *d, const ps_tile *t, const ps_epilogue *e, const void *in_blk,
                                    const void *wt_blk, void *out_blk, void *workspace, size_t workspace_bytes,
                                    void *stream)
@@ -470,6 +521,7 @@ extern "C" const char *ps_strerror(int status)
     case PS_EINVAL: return "invalid argument (null or misaligned pointer, non-positive size, empty output)";
     case PS_EUNSUPPORTED: return "unsupported (K not a multiple of 16, unknown dtype, tensor over 2 GiB, or tile not valid)";
     case PS_EHIP: return "HIP runtime error at kernel launch";
+    case PS_ESCRATCH: return "the tile's partial planes exceed the library's static scratch (PS_STATIC_SCRATCH_BYTES)";
     default: return "unknown status";
     }
 }

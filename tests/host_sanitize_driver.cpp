@@ -96,6 +96,7 @@ static void drive_descriptor(const ps_conv_desc &d, bool expect_valid, bool with
         // the convolution calls refuse before touching a pointer or the device
         CHECK(ps_conv2d_fwd(&d, &t, &t, &t, nullptr) < 0, "ps_conv2d_fwd on a malformed descriptor");
         CHECK(ps_conv2d_fwd_ws(&d, nullptr, &t, &t, &t, nullptr, 0, nullptr) < 0, "ps_conv2d_fwd_ws on a malformed descriptor");
+        CHECK(ps_conv2d_fwd_static(&d, nullptr, &t, &t, &t, nullptr) < 0, "ps_conv2d_fwd_static on a malformed descriptor");
         return;
     }
     CHECK(rc == PS_OK && P > 0 && Q > 0, "valid descriptor refused: rc %d", rc);
@@ -141,7 +142,7 @@ static void drive_descriptor(const ps_conv_desc &d, bool expect_valid, bool with
                            {INT_MAX, INT_MAX, INT_MAX, INT_MAX, 1}, {64, 64, 2, INT_MAX, 0}, {-64, 64, 2, 1, 0}};
     for (const ps_tile &b : bad) {
         CHECK(ps_tile_valid(&d, &b) < 0 && ps_tile_cost_us(&d, &b) < 0 && ps_workspace_bytes(&d, &b) == 0, "bad tile accepted");
-        CHECK(ps_conv2d_fwd_tile(&d, &b, &b, &b, const_cast<ps_tile *>(&b), nullptr) < 0, "bad tile launched");
+        CHECK(ps_conv2d_fwd_static(&d, &b, &b, &b, const_cast<ps_tile *>(&b), nullptr) < 0, "bad tile launched");
     }
     if (with_working_sets) {  // Algorithms 1 and 2 on the tile's workgroup-level nest (enumeration: small shapes only)
         int64_t lvl[PS_RANKER_LEVELS], mem = -1;
@@ -361,11 +362,11 @@ int main()
 
     drive_reuse(rng);
     drive_oracle(rng);
-    CHECK(std::strlen(ps_strerror(-99)) > 0 && std::strlen(ps_last_hip_error()) == 0, "strings");
+    CHECK(std::strlen(ps_strerror(PS_ESCRATCH)) > 0 && std::strlen(ps_strerror(-99)) > 0 && std::strlen(ps_last_hip_error()) == 0, "strings");
     {   // a valid call where no device answers: an error code and the runtime's text, nothing else
         const ps_conv_desc d = desc(1, 16, 8, 8, 16, 3, 3, 1, 1, 0);
         alignas(16) static float buf[16 * 64 * 9];
-        CHECK(ps_conv2d_fwd(&d, buf, buf, buf, nullptr) == PS_EHIP && std::strlen(ps_last_hip_error()) > 0, "no-device call");
+        CHECK(ps_conv2d_fwd_static(&d, nullptr, buf, buf, buf, nullptr) == PS_EHIP && std::strlen(ps_last_hip_error()) > 0, "no-device call");
     }
     std::printf("host sanitizer driver: %d errors\n", g_errors);
     return g_errors == 0 ? 0 : 1;
