@@ -6,25 +6,89 @@
 // here is a pure permutation of bit patterns (plus +0.0 fill of channel lanes past C), so it
 // is generic over the element size and bit-exact.
 //
-// All of them are HBM-bound copies.  Activations go through an LDS transpose so that both
-// the read side (a run of pixels of one channel) and the write side (16 channels of a run of
-// pixels) are contiguous per wavefront.
+// All of them are HBM-bound copies (2 x tensor bytes).  Activations: a lane moves one VE x VE block (VE = 16 bytes /
+// element size: 4 channels x 4 pixels in fp32, 8 x 8 in 16 bits) with 16-byte accesses on both sides and turns it
+// around in registers: VE loads of VE consecutive pixels of one channel each (plain side; the 16 lanes that share a
+// channel read 256 contiguous bytes), VE stores of VE consecutive channels of one pixel each (blocked side; the
+// 16 / VE lanes that share a pixel write its whole 16-channel line, and the VE stores of a wave fill a contiguous
+// range without gaps).  No LDS, no barrier, VE independent loads in flight per lane.  Plain cached accesses: with
+// non-temporal loads or stores the transforms of tensors that stay in the Infinity Cache got 15-25 % slower and those
+// that stream from HBM 2-3 % faster (measured), and a transform's output is normally what the next kernel reads.  Images whose pixel count is
+// not a multiple of VE (7x7; 14x14 in 16 bits) have channel rows that do not start on 16-byte boundaries: they go
+// through the LDS transpose below with element-sized accesses.
 #include "ps_internal.h"
 
 namespace ps {
 namespace {
 
-constexpr int kPix = 256;  // pixels per workgroup tile (= threads per workgroup)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// plain [n][c][hw] -> blocked [n][cb][hw][16]
+// Work item L -> (image and channel block ncb, pixel group pxv, channel group j); j runs fastest so that the lanes of
+// one pixel are neighbours on the blocked side.
+template <typename T, bool kToBlocked>
+__global__ __launch_bounds__(256) void act_blocks_kernel(const T *__restrict__ src, T *__restrict__ dst, int C, int Cb,
+                                                         int HW, unsigned hwv, unsigned magic_hwv, size_t total)
+{
+    constexpr int VE = 16 / (int)sizeof(T);  // elements per 16-byte access
+    constexpr int G = kBlock / VE;           // channel groups per 16-channel block
+    const size_t L = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (L >= total) return;
+    const unsigned j = (unsigned)(L % G);
+    const unsigned rest = (unsigned)(L / G);
+    // rest = ncb * hwv + pxv by reciprocal multiplication (exact for rest < 2^31, see fast_divmod in the convolution)
+    unsigned ncb = __umulhi(rest, magic_hwv);
+    unsigned pxv = rest - ncb * hwv;
+    if (pxv >= hwv) { pxv -= hwv; ++ncb; }
+    const unsigned n = ncb / (unsigned)Cb, cb = ncb - n * (unsigned)Cb;
+    const int c0 = (int)(cb * kBlock + j * VE);                                  // first channel of this lane's group
+    const size_t plain_off = ((size_t)n * C + c0) * HW + (size_t)pxv * VE;       // + e * HW per channel
+    const size_t blk_off = ((size_t)ncb * HW + (size_t)pxv * VE) * kBlock + j * VE;  // + e * 16 per pixel
+    u32x4 v[VE], o[VE];
+    if (kToBlocked) {
+#pragma unroll
+        for (int e = 0; e < VE; ++e) {
+            v[e] = u32x4{0u, 0u, 0u, 0u};  // channel lanes past C hold +0.0
+            if (c0 + e < C) v[e] = *reinterpret_cast<const u32x4 *>(src + plain_off + (size_t)e * HW);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VE; ++e) v[e] = *reinterpret_cast<const u32x4 *>(src + blk_off + (size_t)e * kBlock);
+    }
+    // element b of output vector a = element a of input vector b
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) o[a] = u32x4{v[0][a], v[1][a], v[2][a], v[3][a]};
+    } else {
+#pragma unroll
+        for (int a = 0; a < 8; ++a)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const unsigned lo = v[2 * k][a >> 1], hi = v[2 * k + 1][a >> 1];
+                o[a][k] = (a & 1) ? (lo >> 16) | (hi & 0xFFFF0000u) : (lo & 0xFFFFu) | (hi << 16);
+            }
+    }
+    if (kToBlocked) {
+#pragma unroll
+        for (int e = 0; e < VE; ++e) *reinterpret_cast<u32x4 *>(dst + blk_off + (size_t)e * kBlock) = o[e];
+    } else {
+#pragma unroll
+        for (int e = 0; e < VE; ++e)
+            if (c0 + e < C) *reinterpret_cast<u32x4 *>(dst + plain_off + (size_t)e * HW) = o[e];
+    }
+}
+
+constexpr int kPix = 256;  // pixels per workgroup tile of the LDS-transpose kernels (= threads per workgroup)
+
+// plain [n][c][hw] -> blocked [n][cb][hw][16], any pixel count; workgroup = (image and channel block, pixel tile)
 template <typename T>
 __global__ __launch_bounds__(kPix) void act_to_blocked_kernel(const T *__restrict__ src, T *__restrict__ dst,
-                                                              int C, int Cb, int HW)
+                                                              int C, int Cb, int HW, unsigned ntile)
 {
     __shared__ T tile[kBlock][kPix + 1];
     const int t = threadIdx.x;
-    const int n = blockIdx.y / Cb, cb = blockIdx.y % Cb;
-    const int pix0 = blockIdx.x * kPix;
+    const unsigned ncb = blockIdx.x / ntile;
+    const int n = (int)(ncb / (unsigned)Cb), cb = (int)(ncb % (unsigned)Cb);
+    const int pix0 = (int)(blockIdx.x % ntile) * kPix;
     const int npix = min(kPix, HW - pix0);
 #pragma unroll
     for (int c = 0; c < kBlock; ++c) {
@@ -43,15 +107,16 @@ __global__ __launch_bounds__(kPix) void act_to_blocked_kernel(const T *__restric
     }
 }
 
-// blocked [n][cb][hw][16] -> plain [n][c][hw]
+// blocked [n][cb][hw][16] -> plain [n][c][hw], any pixel count
 template <typename T>
 __global__ __launch_bounds__(kPix) void blocked_to_act_kernel(const T *__restrict__ src, T *__restrict__ dst,
-                                                              int C, int Cb, int HW)
+                                                              int C, int Cb, int HW, unsigned ntile)
 {
     __shared__ T tile[kBlock][kPix + 1];
     const int t = threadIdx.x;
-    const int n = blockIdx.y / Cb, cb = blockIdx.y % Cb;
-    const int pix0 = blockIdx.x * kPix;
+    const unsigned ncb = blockIdx.x / ntile;
+    const int n = (int)(ncb / (unsigned)Cb), cb = (int)(ncb % (unsigned)Cb);
+    const int pix0 = (int)(blockIdx.x % ntile) * kPix;
     const int npix = min(kPix, HW - pix0);
     const T *in = src + (((size_t)n * Cb + cb) * HW + pix0) * kBlock;
     const int nel = npix * kBlock;
@@ -99,13 +164,27 @@ __global__ __launch_bounds__(256) void filt_kernel(const T *__restrict__ src, T 
 template <typename T>
 int run_act(bool to_blocked, const void *src, void *dst, int N, int C, int HW, hipStream_t st)
 {
+    constexpr int VE = 16 / (int)sizeof(T);
     const int Cb = (C + kBlock - 1) / kBlock;
-    dim3 grid((HW + kPix - 1) / kPix, (unsigned)(N * Cb));
-    if ((long long)N * Cb > 65535) return PS_EUNSUPPORTED;
+    if (HW % VE == 0) {  // every channel row starts on a 16-byte boundary: register-transposed blocks
+        const unsigned hwv = (unsigned)(HW / VE);
+        const size_t total = (size_t)N * Cb * hwv * (kBlock / VE);  // < 2^31 / 64: the tensors stay below 2 GiB
+        const unsigned magic = hwv == 1 ? 0xFFFFFFFFu : (unsigned)((1ULL << 32) / hwv);
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (to_blocked)
+            hipLaunchKernelGGL((act_blocks_kernel<T, true>), grid, dim3(256), 0, st, (const T *)src, (T *)dst, C, Cb, HW, hwv,
+                               magic, total);
+        else
+            hipLaunchKernelGGL((act_blocks_kernel<T, false>), grid, dim3(256), 0, st, (const T *)src, (T *)dst, C, Cb, HW, hwv,
+                               magic, total);
+        return hip_status(hipGetLastError());
+    }
+    const unsigned ntile = (unsigned)((HW + kPix - 1) / kPix);
+    const dim3 grid((unsigned)((size_t)N * Cb * ntile));  // <= tensor elements / 16: fits 32 bits
     if (to_blocked)
-        hipLaunchKernelGGL(act_to_blocked_kernel<T>, grid, dim3(kPix), 0, st, (const T *)src, (T *)dst, C, Cb, HW);
+        hipLaunchKernelGGL(act_to_blocked_kernel<T>, grid, dim3(kPix), 0, st, (const T *)src, (T *)dst, C, Cb, HW, ntile);
     else
-        hipLaunchKernelGGL(blocked_to_act_kernel<T>, grid, dim3(kPix), 0, st, (const T *)src, (T *)dst, C, Cb, HW);
+        hipLaunchKernelGGL(blocked_to_act_kernel<T>, grid, dim3(kPix), 0, st, (const T *)src, (T *)dst, C, Cb, HW, ntile);
     return hip_status(hipGetLastError());
 }
 

@@ -14,6 +14,8 @@ SHAPES = [
     wl.ConvShape(3, 64, 14, 14, 64, 3, 3, 1, 1),
     wl.ConvShape(2, 16, 1, 1, 48, 1, 1, 1, 0),        # single pixel
     wl.ConvShape(1, 128, 28, 28, 16, 1, 1, 2, 0),     # strided: output smaller than input
+    wl.ConvShape(300, 4096, 2, 2, 16, 1, 1, 1, 0),    # 76800 (image, channel block) pairs: more than one grid dimension holds
+    wl.ConvShape(2, 24, 16, 24, 32, 1, 1, 1, 0),      # pixel count a multiple of 8: 16-byte blocks in both element sizes, ragged C
 ]
 
 
