@@ -171,6 +171,10 @@ int ps_tile_select_ws(const ps_conv_desc *d, size_t workspace_bytes, ps_tile *be
  * ps_tile_select_ws returns.  Timing the k tiles is the caller's part (paper_2002_02145_amd.autotune.run_top_k). */
 int ps_tile_rank_ws(const ps_conv_desc *d, size_t workspace_bytes, int k, ps_tile *tiles, double *modelled_us);
 
+/* Environment (read when a descriptor is first ranked by a convolution call or ps_tile_pick, then cached with the pick):
+ *   PS_FORCE_TILE="kt,mt,ring,c_split,raster"  use this tile wherever it is valid (and its workspace fits) instead of
+ *                                              the model's pick: a way to pin or A/B a tile without changing callers;
+ *   PS_DUMP_RANKING=k                          print the k best candidates and their modelled times to stderr. */
 /* The tile the convolution calls run when none is passed: ps_conv2d_fwd (with_workspace = 0, ranking of
  * ps_tile_select) or ps_conv2d_fwd_ws / ps_conv2d_fwd_fused with t == NULL (with_workspace != 0, ranking of
  * ps_tile_select_ws for `workspace_bytes`).  The ranking of Section 4.2 depends on the descriptor alone, so the

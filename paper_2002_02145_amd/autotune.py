@@ -113,27 +113,58 @@ def run_top_k(desc: ps.ConvDesc, k: int, workspace: torch.Tensor, sets=None, min
     return best[0], best[2], rows
 
 
+def stored_row(result: dict, N: int) -> dict:
+    """The compact form sweeps are kept in under data/: one line per layer, a row [kt, mt, ring, c_split, raster, us]
+    per candidate."""
+    return {"layer": result["layer"], "N": N, "dtype": result["dtype"],
+            "rows": [list(r["tile"]) + [round(r["us"], 3)] for r in result["rows"]]}
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__)
-    ap.add_argument("--layers", default="sweep", help="sweep | cfg1 | cfg2 | cfg3a | cfg3b | comma list of layer names")
+    ap.add_argument("--layers", default="sweep",
+                    help="sweep (the ResNet-50-shaped set) | heldout | validation (the two out-of-sample sets) | cfg1 | cfg2 | cfg3a | cfg3b | "
+                         "comma list of layer names")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--batch", type=int, default=wl.MINIBATCH, help="mini-batch size of the named layer sets")
     ap.add_argument("--min-ms", type=float, default=20.0)
     ap.add_argument("--cold", action="store_true", help="rotate buffers so every launch streams from HBM")
     ap.add_argument("--rows", action="store_true", help="include every candidate's time in the output")
     ap.add_argument("--atomics", action="store_true",
                     help="time split reductions through ps_conv2d_fwd_tile (clear + atomics) instead of the workspace path")
     ap.add_argument("--out", default=None)
+    ap.add_argument("--store", default=None,
+                    help="append each layer's sweep in the compact stored form to this file; layers already in the file "
+                         "are skipped, so an interrupted sweep resumes where it stopped")
     a = ap.parse_args(argv)
+    N = a.batch
+    rebatch = lambda L: wl.ConvShape(N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.name)
     named = {"cfg1": wl.CFG1, "cfg2": wl.CFG2, "cfg3a": wl.CFG3A, "cfg3b": wl.CFG3B}
-    named.update({l.name: l for l in wl.resnet50_layers()})
+    named.update({l.name: l for l in wl.resnet50_layers(N) + wl.heldout_layers(N) + wl.validation_layers(N) + [rebatch(wl.CFG3B)]})
     if a.layers == "sweep":
-        layers = wl.resnet50_layers() + [wl.CFG3B]
+        layers = wl.resnet50_layers(N) + [rebatch(wl.CFG3B)]
+    elif a.layers == "heldout":
+        layers = wl.heldout_layers(N)
+    elif a.layers == "validation":
+        layers = wl.validation_layers(N)
     else:
         layers = [named[n] for n in a.layers.split(",")]
     dtype = ps.PS_F32 if a.dtype == "f32" else ps.PS_BF16
+    done = set()
+    if a.store:
+        try:
+            done = {json.loads(l)["layer"] for l in open(a.store) if l.strip()}
+        except FileNotFoundError:
+            pass
     out = open(a.out, "w") if a.out else sys.stdout
     for shape in layers:
+        if shape.name in done:
+            print(f"{shape.name}: already stored, skipped", file=sys.stderr, flush=True)
+            continue
         r = sweep(shape, dtype, a.min_ms, a.cold, use_ws=not a.atomics)
+        if a.store:
+            with open(a.store, "a") as f:
+                f.write(json.dumps(stored_row(r, shape.N), separators=(",", ":")) + "\n")
         if not a.rows:
             r.pop("rows")
         print(json.dumps(r), file=out, flush=True)

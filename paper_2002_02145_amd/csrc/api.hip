@@ -1,6 +1,8 @@
 // C ABI entry points: descriptor validation, size queries, convolution launch.
 #include <algorithm>
 #include <atomic>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <shared_mutex>
@@ -51,9 +53,9 @@ int make_dims(const ps_conv_desc *d, Dims *o)
     return PS_OK;
 }
 
-// 7x7 filter over at most 4 input channels (a network stem): the fp32 kernels pack 4 taps x 4 channels into
-// one 16-lane batch element.
-bool packs_taps(const Dims &dm) { return dm.dtype == PS_F32 && dm.C <= 4 && dm.R == 7 && dm.S == 7; }
+// 7x7 filter over few input channels (a network stem): the fp32 kernels pack 4 taps x 4 channels into one 16-lane
+// batch element (C <= 4), the 16-bit ones 2 taps x 8 channels (C <= 8).
+bool packs_taps(const Dims &dm) { return dm.C <= (dm.dtype == PS_F32 ? 4 : 8) && dm.R == 7 && dm.S == 7; }
 
 const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 {
@@ -62,6 +64,14 @@ const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
     for (int i = 0; i < n; ++i)
         if (tab[i].kt == kt && tab[i].mt == mt && tab[i].ring == ring) return &tab[i];
     return nullptr;
+}
+
+// Output channels are padded to whole 32-wide MFMA tiles anyway; a channel tile kt may add to that padding at most a
+// quarter of what it then covers (K = 96 runs as two 64-channel tiles, K = 64 never as one 128-channel tile).
+bool kt_admissible(int K, int kt)
+{
+    const int padded = (K + kt - 1) / kt * kt, base = (K + 31) / 32 * 32;
+    return padded == base || (padded - base) * 4 <= padded;
 }
 
 struct ShapeInfo {
@@ -92,8 +102,7 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     // pixel-stationary shapes: 1x1 filters over exactly 4 c-blocks, images of at least 16 pixels
     if (sh->stationary && !(dm.R == 1 && dm.S == 1 && t.c_split == 1 && dm.Cb == 4 && dm.P * dm.Q >= 16))
         return PS_EUNSUPPORTED;
-    // output channels are padded to whole 32-wide MFMA tiles at most: a larger kt would only add waste
-    if ((dm.K + t.kt - 1) / t.kt * t.kt != (dm.K + 31) / 32 * 32) return PS_EUNSUPPORTED;
+    if (!kt_admissible(dm.K, t.kt)) return PS_EUNSUPPORTED;
     if (dm.NB % t.c_split != 0) return PS_EUNSUPPORTED;
     const long long n_mt = (dm.M + t.mt - 1) / t.mt;
     if (n_mt * ((dm.K + t.kt - 1) / t.kt) * t.c_split > (1LL << 30)) return PS_EUNSUPPORTED;
@@ -185,7 +194,7 @@ int build_plan(const Dims &dm, const ps_tile &t, Plan *pl)
     case PS_KERNEL_PATCH_3X3: pl->fn = sh->launch_halo; break;
     case PS_KERNEL_PACKED_7X7:
         pl->fn = sh->launch_7x7p;
-        a.nb_split = 13;  // 49 taps, four per batch element; a.NB stays 49 for filter addressing
+        a.nb_split = dm.dtype == PS_F32 ? 13 : 25;  // 49 taps, four (two) per batch element; a.NB stays 49 for filter addressing
         break;
     default: break;
     }
@@ -267,6 +276,35 @@ CacheKey key_of(const ps_conv_desc &d)
     return k;
 }
 
+// Two environment variables, read when a descriptor is first ranked (the result is cached like any other pick):
+//   PS_FORCE_TILE="kt,mt,ring,c_split,raster"  runs that tile on every descriptor it is valid for (and whose
+//                                              workspace it fits) instead of the model's pick;
+//   PS_DUMP_RANKING=k                          prints the k best candidates with their modelled times to stderr.
+void apply_env_overrides(const ps_conv_desc *d, const Dims &dm, int mode, size_t ws_bytes, Pick *p)
+{
+    if (const char *dump = std::getenv("PS_DUMP_RANKING")) {
+        const int k = std::max(1, std::min(64, std::atoi(dump)));
+        ps_tile tiles[64];
+        double us[64];
+        const int n = ps_tile_rank_ws(d, mode ? ws_bytes : 0, k, tiles, us);
+        std::fprintf(stderr, "ps ranking N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d dtype=%d (%s)\n", d->N, d->C, d->H,
+                     d->W, d->K, d->R, d->S, d->stride, d->pad, d->dtype, mode ? "workspace" : "no workspace: unsplit tiles shown");
+        for (int i = 0; i < n; ++i)
+            std::fprintf(stderr, "  %2d  kt=%d mt=%d ring=%d c_split=%d raster=%d  %.2f us\n", i + 1, tiles[i].kt, tiles[i].mt,
+                         tiles[i].ring, tiles[i].c_split, tiles[i].raster, us[i]);
+    }
+    if (const char *force = std::getenv("PS_FORCE_TILE")) {
+        ps_tile t;
+        if (std::sscanf(force, "%d,%d,%d,%d,%d", &t.kt, &t.mt, &t.ring, &t.c_split, &t.raster) == 5 && tile_valid(dm, t) == PS_OK) {
+            const size_t need = t.c_split > 1 ? (size_t)t.c_split * (size_t)dm.M * dm.K * 4 : 0;
+            if (!mode || need <= ws_bytes) {
+                p->t = t;
+                p->modelled_us = mode ? ps_tile_cost_ws_us(d, &t) : ps_tile_cost_us(d, &t);
+            }
+        }
+    }
+}
+
 // The pick for a descriptor: mode 0 = ps_tile_select (split reductions by atomics), mode 1 = ps_tile_select_ws.  What a
 // workspace size decides is how many partial planes fit (splits go up to 16), so that count is the key, not the
 // byte count.
@@ -280,8 +318,9 @@ int cached_pick(const ps_conv_desc *d, const Dims &dm, int mode, size_t ws_bytes
         return PS_OK;
     }
     Pick p;
-    const int rc = mode ? ps_tile_select_ws(d, ws_bytes, &p.t, &p.modelled_us) : ps_tile_select(d, &p.t, &p.modelled_us);
+    int rc = mode ? ps_tile_select_ws(d, ws_bytes, &p.t, &p.modelled_us) : ps_tile_select(d, &p.t, &p.modelled_us);
     if (rc != PS_OK) return rc;
+    apply_env_overrides(d, dm, mode, ws_bytes, &p);
     pick_cache().publish(k, p);
     *t = p.t;
     return PS_OK;

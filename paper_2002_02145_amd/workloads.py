@@ -85,6 +85,40 @@ def resnet50_layers(N: int = MINIBATCH) -> list[ConvShape]:
     return layers
 
 
+def heldout_layers(N: int = MINIBATCH) -> list[ConvShape]:
+    """Layer shapes of the kind the paper's other networks have (Section 5.1 lists AlexNet, OverFeat, GoogLeNet and
+    others besides ResNet-50, without tabulating their layers): channel widths that are not powers of two, 5x5 and
+    11x11 filters, a strided 3x3, odd image sizes.  Synthetic stand-ins chosen here, not taken from the paper.  The
+    tile model's constants were never tuned on them: they are the out-of-sample check of its ranking."""
+    return [
+        ConvShape(N, 96, 27, 27, 96, 3, 3, 1, 1, "3x3_96_27"),
+        ConvShape(N, 192, 13, 13, 192, 3, 3, 1, 1, "3x3_192_13"),
+        ConvShape(N, 384, 13, 13, 384, 3, 3, 1, 1, "3x3_384_13"),
+        ConvShape(N, 48, 27, 27, 128, 5, 5, 1, 2, "5x5_48to128_27"),
+        ConvShape(N, 128, 56, 56, 128, 3, 3, 2, 1, "3x3s2_128_56"),
+        ConvShape(N, 192, 28, 28, 64, 1, 1, 1, 0, "1x1_192to64_28"),
+        ConvShape(N, 480, 14, 14, 192, 1, 1, 1, 0, "1x1_480to192_14"),
+        ConvShape(N, 3, 227, 227, 64, 11, 11, 4, 0, "11x11s4_3to64_227"),
+    ]
+
+
+def validation_layers(N: int = MINIBATCH) -> list[ConvShape]:
+    """A third layer set of the same kind as heldout_layers (GoogLeNet-like widths such as 160, 208, 320 and 832, a 5x5
+    over 32 channels, a strided 3x3, a 7x7 stem with 96 output channels).  heldout_layers exposed one weakness of the
+    tile model, which was then changed; this set was swept only after that change and nothing was ever adjusted on
+    it."""
+    return [
+        ConvShape(N, 160, 28, 28, 160, 3, 3, 1, 1, "3x3_160_28"),
+        ConvShape(N, 320, 14, 14, 320, 3, 3, 1, 1, "3x3_320_14"),
+        ConvShape(N, 32, 14, 14, 96, 5, 5, 1, 2, "5x5_32to96_14"),
+        ConvShape(N, 256, 28, 28, 256, 3, 3, 2, 1, "3x3s2_256_28"),
+        ConvShape(N, 96, 14, 14, 208, 1, 1, 1, 0, "1x1_96to208_14"),
+        ConvShape(N, 832, 7, 7, 256, 1, 1, 1, 0, "1x1_832to256_7"),
+        ConvShape(N, 1280, 7, 7, 320, 1, 1, 1, 0, "1x1_1280to320_7"),
+        ConvShape(N, 3, 224, 224, 96, 7, 7, 2, 3, "stem_7x7s2_3to96_224"),
+    ]
+
+
 def sweep_seed(layer_index: int) -> int:
     return 100 + layer_index
 
