@@ -452,16 +452,6 @@ void launch_bf16_packed7(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
     hipLaunchKernelGGL((conv_fwd_bf16_packed7_kernel<KT, MT, WK, WM, NBUF, G>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
-// only tile shapes a 64-channel stem can use get the kernel (kt <= 64)
-template <int KT, int MT, int WK, int WM, int NBUF, int G>
-constexpr LaunchFn packed7_launch_or_null()
-{
-    if constexpr (KT <= 64)
-        return &launch_bf16_packed7<KT, MT, WK, WM, NBUF, G>;
-    else
-        return nullptr;
-}
-
 template <int KT, int MT, int WK, int WM, int NBUF, int G, int SIDE>
 void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
 {
@@ -472,7 +462,7 @@ void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
 #define PS_BF16_SHAPE(KT, MT, WK, WM, NBUF, G)                                                          \
     {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES, G,              \
      &launch_bf16<KT, MT, WK, WM, NBUF, G, 0>, &launch_bf16<KT, MT, WK, WM, NBUF, G, 1>,                 \
-     &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, packed7_launch_or_null<KT, MT, WK, WM, NBUF, G>(),           \
+     &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, &launch_bf16_packed7<KT, MT, WK, WM, NBUF, G>,           \
      halo_launch_or_null<KT, MT, WK, WM, NBUF>(),                                                        \
      halo_capacity_bytes<MT>(), 0, Bf16Shape<KT, MT, WK, WM, NBUF, 3>::LDS_BYTES,                        \
      halo_lds_bytes_or_zero<KT, MT, WK, WM, NBUF>()}

@@ -52,6 +52,11 @@ def params_path(kind: int, dtype: str) -> str:
     return os.path.join(DATA, f"ranker_{dtype}_{_kind_name(kind)}.json")
 
 
+def held_out_params_path(kind: int, dtype: str) -> str:
+    """Parameters of the leave-one-layer-out networks (one float32 [PS_RANKER_PARAMS] array per batch-28 layer)."""
+    return os.path.join(DATA, f"ranker_{dtype}_{_kind_name(kind)}_leave_one_out.npz")
+
+
 def load_params(kind: int, dtype: str = "f32") -> np.ndarray:
     """Stored parameters as float32 [PS_RANKER_PARAMS] in the library's flat layout."""
     with open(params_path(kind, dtype)) as f:
@@ -183,12 +188,15 @@ def train(dtype: str, kind: int, epochs: int = 40, seed: int = 0, held_out: bool
     sweeps = load_sweeps(dtype, kind)
     report = {}
     if held_out:
+        loo = {}
         for name, N, _, stats, us in sweeps:
             if N != wl.MINIBATCH:
                 continue
-            _, _, net = _fit([s for s in sweeps if s[0] != name], epochs, seed)
+            loo[name], _, net = _fit([s for s in sweeps if s[0] != name], epochs, seed)
             report[name] = round(_pick_loss_cpu(net, stats, us), 4)
             print(json.dumps({"held_out_layer": name, "pick_vs_best": report[name]}), file=out, flush=True)
+        # kept so that `evaluate --held-out` can play these networks' tournaments in the GPU library
+        np.savez_compressed(held_out_params_path(kind, dtype), **loo)
     params, acc, _ = _fit(sweeps, epochs, seed)
     blob = {"kind": _kind_name(kind), "dtype": dtype, "theta": THETA, "widths": list(WIDTHS),
             "layout": "per layer: weights [inputs][units] row-major, then bias",
@@ -202,12 +210,14 @@ def train(dtype: str, kind: int, epochs: int = 40, seed: int = 0, held_out: bool
     return blob
 
 
-def evaluate(dtype: str, kind: int, out=sys.stdout) -> dict:
+def evaluate(dtype: str, kind: int, out=sys.stdout, held_out: bool = False) -> dict:
     """Ranks every stored batch-28 layer with ps_tile_rank_dnn (GPU) and compares the pick with the sweep's best and
-    with the tile model's pick."""
+    with the tile model's pick.  held_out: each layer is ranked by the network that was trained without that layer (at
+    any batch size) instead of the shipped one -- the same library call, other parameters."""
     import torch
     dt = ps.PS_F32 if dtype == "f32" else ps.PS_BF16
     params = torch.from_numpy(load_params(kind, dtype)).to("cuda:0")
+    loo = np.load(held_out_params_path(kind, dtype)) if held_out else None
     worst = worst_model = 0.0
     rows = []
     for line in open(os.path.join(DATA, SWEEPS[dtype][0])):
@@ -217,6 +227,8 @@ def evaluate(dtype: str, kind: int, out=sys.stdout) -> dict:
         us = {tuple(row[:5]): row[5] for row in r["rows"]}
         best = min(us.values())
         scratch = torch.empty(ps.ps_tile_rank_dnn_scratch_bytes(d), dtype=torch.uint8, device="cuda:0")
+        if loo is not None:
+            params = torch.from_numpy(np.ascontiguousarray(loo[r["layer"]], dtype=np.float32)).to("cuda:0")
         t0 = time.perf_counter()
         ranked = ps.ps_tile_rank_dnn(d, 1 << 40, kind, params, THETA, scratch, scratch.numel(), 3)
         rank_ms = (time.perf_counter() - t0) * 1e3          # statistics on the host, copies, tournament, sort
@@ -244,7 +256,8 @@ def evaluate(dtype: str, kind: int, out=sys.stdout) -> dict:
         worst, worst_model = max(worst, row["pick_vs_best"]), max(worst_model, row["model_pick_vs_best"])
         rows.append(row)
         print(json.dumps(row), file=out)
-    summary = {"dtype": dtype, "kind": _kind_name(kind), "layers": len(rows), "worst_pick_vs_best": worst,
+    summary = {"dtype": dtype, "kind": _kind_name(kind), "networks": "leave-one-layer-out" if held_out else "shipped",
+               "layers": len(rows), "worst_pick_vs_best": worst,
                "mean_pick_vs_best": round(sum(r["pick_vs_best"] for r in rows) / len(rows), 4),
                "worst_model_pick_vs_best": worst_model}
     print(json.dumps({"summary": summary}), file=out)
@@ -258,12 +271,14 @@ def main(argv=None) -> int:
     ap.add_argument("--kind", default="level_times", choices=sorted(KINDS))
     ap.add_argument("--epochs", type=int, default=40)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--no-held-out", action="store_true")
+    ap.add_argument("--no-held-out", action="store_true", help="train: skip the leave-one-layer-out networks")
+    ap.add_argument("--held-out", action="store_true",
+                    help="evaluate: rank each layer with the network trained without it (GPU tournament as always)")
     a = ap.parse_args(argv)
     if a.command == "train":
         train(a.dtype, KINDS[a.kind], a.epochs, a.seed, not a.no_held_out)
     else:
-        evaluate(a.dtype, KINDS[a.kind])
+        evaluate(a.dtype, KINDS[a.kind], held_out=a.held_out)
     return 0
 
 

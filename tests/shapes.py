@@ -19,4 +19,6 @@ EDGE_SHAPES = [
     ConvShape(2, 50, 10, 10, 512, 1, 1, 2, 0, "1x1_C50_K512_stride2"),  # the same with zero lanes, two channel groups
     ConvShape(2, 3, 20, 17, 64, 7, 7, 2, 3, "stem_like_K64"),           # tap-packed 7x7 in the 16x16-tile kernels too
     ConvShape(1, 64, 5, 5, 240, 1, 1, 1, 1, "1x1_64to240_pad1"),        # ... last channel block missing, padded border
+    ConvShape(2, 3, 18, 15, 128, 7, 7, 2, 3, "stem_like_K128"),         # tap-packed 7x7 on the wide channel tiles
+    ConvShape(1, 7, 11, 12, 96, 7, 7, 1, 3, "7x7_C7_K96"),              # 16-bit packing uses 8 channel lanes; K = 96 pads a 64-wide tile
 ]

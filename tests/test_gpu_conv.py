@@ -126,6 +126,19 @@ def test_resnet50_sweep(dtype):
             assert abs(got[nn, k, p, q] - o) <= TOL[dtype] * m, shape.name
 
 
+@pytest.mark.parametrize("dtype", [0, 1], ids=["fp32", "bf16"])
+def test_out_of_sample_layer_sets(dtype):
+    """The layers of the two out-of-sample sets (other widths, 5x5 and 11x11 filters, strided 3x3, a 96-channel stem)
+    at N = 28 with the library's pick: every output element against the oracle."""
+    from gpu_util import run_conv
+    for i, shape in enumerate(wl.heldout_layers() + wl.validation_layers()):
+        x, w = _prep(shape, wl.relu_like, 200 + i, dtype)
+        got = run_conv(shape, x, w, dtype, ws=True)
+        out, mag = oracle.conv2d_fwd(shape, x, w)
+        err = oracle.normalised_error(got, out, mag)
+        assert err <= TOL[dtype], f"{shape.name}: {err}"
+
+
 @pytest.mark.parametrize("shape", [
     # blocked input of 2 * 4 * 2040 * 2040 * 64 B = 0.992 * 2^31 bytes: the largest byte offsets the kernels form
     wl.ConvShape(2, 64, 2040, 2040, 16, 1, 1, 2, 0, "input_near_2GiB"),
@@ -158,7 +171,7 @@ def test_every_candidate_tile_at_full_size(dtype):
     import torch
     from gpu_util import DEV, all_tiles, blocked_inputs
     from paper_2002_02145_amd import binding as ps
-    for i, shape in enumerate(wl.resnet50_layers() + [wl.CFG3B]):
+    for i, shape in enumerate(wl.resnet50_layers() + [wl.CFG3B] + wl.heldout_layers()):
         x, w = _prep(shape, wl.relu_like, wl.sweep_seed(i), dtype)
         d, xb, wb = blocked_inputs(shape, x, w, dtype)
         n_out = ps.ps_blocked_out_bytes(d) // 4

@@ -52,6 +52,12 @@ def test_pick_is_close_to_the_sweeps_best(fname, dtype, worst, mean):
     # before the model told L2-resident layers from larger ones (load latency); the 16-bit 5x5 layer stands at 10.3 %.
     ("sweep_f32_heldout_N28.jsonl", ps.PS_F32, 0.10, 0.03),
     ("sweep_bf16_heldout_N28.jsonl", ps.PS_BF16, 0.11, 0.04),
+    # a second such set, first swept with everything frozen: fp32 66 % on 5x5 32->96 at 14x14 (two-wave workgroups,
+    # whose waves the hardware does not spread evenly over the SIMDs: now modelled as measured) and 13.8 % on
+    # 1x1 1280->320 at 7x7 (a split reduction priced too high: still there); 16 bits 46 % on the 96-channel 7x7 stem
+    # (no tap-packed kernel for 128-wide channel tiles: now built) and 13.5 % on the 5x5 layer.
+    ("sweep_f32_validation_N28.jsonl", ps.PS_F32, 0.14, 0.035),
+    ("sweep_bf16_validation_N28.jsonl", ps.PS_BF16, 0.10, 0.02),
 ])
 def test_pick_on_layers_the_model_was_not_calibrated_on(fname, dtype, worst, mean):
     loss = _losses(fname, dtype)
