@@ -187,6 +187,17 @@ int ps_tile_rank_ws(const ps_conv_desc *d, size_t workspace_bytes, int k, ps_til
 int ps_tile_pick(const ps_conv_desc *d, int with_workspace, size_t workspace_bytes, ps_tile *t);
 size_t ps_tile_cache_entries(void);
 
+/* Section 4.2's protocol carried out by the library itself: the n variants are ranked by the model, the best k (at most
+ * 16) are run on the target, the fastest is kept.  The candidates are those of ps_tile_rank_ws for `workspace_bytes`;
+ * each is launched on the caller's blocked tensors a few times and timed with events on `stream` (out_blk ends up
+ * holding the convolution's result; workspace as for ps_conv2d_fwd_ws, NULL if none is lent).  The winner replaces the
+ * descriptor's entry in the per-process table, so later convolution calls with t == NULL and a workspace of the same
+ * class run it (and ps_conv2d_fwd too, if the winner is not a split tile).  This is the one convolution-side call that
+ * waits for its stream: use it at set-up, not in the serving path.  Returns the number of candidates timed, or a
+ * negative ps_status; *best and *best_us (either may be NULL) receive the winner and its microseconds per launch. */
+int ps_tile_autotune(const ps_conv_desc *d, int k, const void *in_blk, const void *wt_blk, void *out_blk, void *workspace,
+                     size_t workspace_bytes, void *stream, ps_tile *best, double *best_us);
+
 /* Which inner loop the library runs for tile `t` on `d` (for reports and tests): the loop with a runtime filter size,
  * the loops with a 1x1 or 3x3 filter baked in, the 7x7 loop that packs four taps of up to four channels into one
  * batch element, the 16-bit 3x3 loop that stages the input patch once per c-block, or the fp32 1x1 loop that keeps a

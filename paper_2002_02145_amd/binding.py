@@ -110,6 +110,7 @@ def _load() -> ctypes.CDLL:
         "ps_tile_kernel": (ctypes.c_int, [dp, tp]),
         "ps_tile_pick": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_size_t, tp]),
         "ps_tile_cache_entries": (ctypes.c_size_t, []),
+        "ps_tile_autotune": (ctypes.c_int, [dp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_size_t, vp, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_tile_cost_ws_us": (ctypes.c_double, [dp, tp]),
         "ps_tile_select_ws": (ctypes.c_int, [dp, ctypes.c_size_t, tp, ctypes.POINTER(ctypes.c_double)]),
         "ps_probe_mfma": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]),
@@ -259,6 +260,18 @@ def ps_tile_pick(desc: ConvDesc, with_workspace: bool = False, workspace_bytes: 
     _check(lib.ps_tile_pick(ctypes.byref(desc), int(bool(with_workspace)), int(workspace_bytes), ctypes.byref(t)),
            "ps_tile_pick")
     return t
+
+
+def ps_tile_autotune(desc: ConvDesc, k: int, in_blk, wt_blk, out_blk, workspace=None, workspace_bytes: int = 0,
+                     stream=None) -> tuple[Tile, float, int]:
+    """Runs the model's k best tiles on the given tensors and makes the fastest the descriptor's pick; returns
+    (tile, microseconds per launch, candidates timed).  Waits for the stream."""
+    t, us = Tile(), ctypes.c_double()
+    n = lib.ps_tile_autotune(ctypes.byref(desc), int(k), _ptr(in_blk), _ptr(wt_blk), _ptr(out_blk), _ptr(workspace) or None,
+                             int(workspace_bytes), _stream(stream), ctypes.byref(t), ctypes.byref(us))
+    if n < 0:
+        raise PsError(n, "ps_tile_autotune")
+    return t, us.value, n
 
 
 def ps_tile_cache_entries() -> int:

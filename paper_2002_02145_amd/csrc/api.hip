@@ -207,8 +207,9 @@ int build_plan(const Dims &dm, const ps_tile &t, Plan *pl)
 // Tile selection enumerates and prices every candidate (tens of microseconds, as long as the kernels it
 // selects for), and preparing a launch walks the shape table and, for the patch kernels, every pixel tile.  Both
 // depend on the descriptor alone, so each result is computed on first use and kept for the life of the process:
-// entries are never changed or removed once published, readers take a shared lock, and a full table simply stops
-// taking new entries (the call then computes its answer as before).
+// prepared launches are never changed or removed once published; a pick changes only when ps_tile_autotune replaces it
+// with a measured winner (readers copy it out under a shared lock); a full table simply stops taking new entries (the
+// call then computes its answer as before).
 struct CacheKey {
     int32_t v[16];
     bool operator==(const CacheKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
@@ -239,6 +240,28 @@ public:
         if (it != map_.end()) return &it->second;
         if (map_.size() >= kMaxEntries) return nullptr;
         return &map_.emplace(k, v).first->second;
+    }
+    // Copy of the entry, taken under the lock (for entries that replace() may change).
+    bool lookup(const CacheKey &k, V *out)
+    {
+        std::shared_lock<std::shared_mutex> lk(mu_);
+        auto it = map_.find(k);
+        if (it == map_.end()) return false;
+        *out = it->second;
+        return true;
+    }
+    // Sets the entry, new or not (false if the table is full and the key is new).
+    bool replace(const CacheKey &k, const V &v)
+    {
+        std::unique_lock<std::shared_mutex> lk(mu_);
+        auto it = map_.find(k);
+        if (it != map_.end()) {
+            it->second = v;
+            return true;
+        }
+        if (map_.size() >= kMaxEntries) return false;
+        map_.emplace(k, v);
+        return true;
     }
     size_t size()
     {
@@ -308,16 +331,22 @@ void apply_env_overrides(const ps_conv_desc *d, const Dims &dm, int mode, size_t
 // The pick for a descriptor: mode 0 = ps_tile_select (split reductions by atomics), mode 1 = ps_tile_select_ws.  What a
 // workspace size decides is how many partial planes fit (splits go up to 16), so that count is the key, not the
 // byte count.
-int cached_pick(const ps_conv_desc *d, const Dims &dm, int mode, size_t ws_bytes, ps_tile *t)
+CacheKey pick_key(const ps_conv_desc *d, const Dims &dm, int mode, size_t ws_bytes)
 {
     CacheKey k = key_of(*d);
     k.v[10] = mode;
     k.v[11] = mode ? (int32_t)std::min<size_t>(16, ws_bytes / ((size_t)dm.M * dm.K * 4)) : 0;
-    if (const Pick *p = pick_cache().find(k)) {
-        *t = p->t;
+    return k;
+}
+
+int cached_pick(const ps_conv_desc *d, const Dims &dm, int mode, size_t ws_bytes, ps_tile *t)
+{
+    const CacheKey k = pick_key(d, dm, mode, ws_bytes);
+    Pick p;
+    if (pick_cache().lookup(k, &p)) {
+        *t = p.t;
         return PS_OK;
     }
-    Pick p;
     int rc = mode ? ps_tile_select_ws(d, ws_bytes, &p.t, &p.modelled_us) : ps_tile_select(d, &p.t, &p.modelled_us);
     if (rc != PS_OK) return rc;
     apply_env_overrides(d, dm, mode, ws_bytes, &p);
@@ -527,6 +556,64 @@ extern "C" int ps_tile_pick(const ps_conv_desc *d, int with_workspace, size_t wo
     if (rc != PS_OK) return rc;
     if (!t) return PS_EINVAL;
     return cached_pick(d, dm, with_workspace ? 1 : 0, with_workspace ? workspace_bytes : 0, t);
+}
+
+extern "C" int ps_tile_autotune(const ps_conv_desc *d, int k, const void *in_blk, const void *wt_blk, void *out_blk,
+                                void *workspace, size_t workspace_bytes, void *stream, ps_tile *best, double *best_us)
+{
+    Dims dm;
+    int rc = make_dims(d, &dm);
+    if (rc != PS_OK) return rc;
+    if (k <= 0 || !in_blk || !wt_blk || !out_blk) return PS_EINVAL;
+    if (!aligned16(in_blk) || !aligned16(wt_blk) || !aligned16(out_blk) || !aligned16(workspace)) return PS_EINVAL;
+    k = std::min(k, 16);
+    ps_tile tiles[16];
+    const size_t ws_bytes = workspace ? workspace_bytes : 0;
+    const int n = ps_tile_rank_ws(d, ws_bytes, k, tiles, nullptr);
+    if (n < 0) return n;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if ((rc = hip_status(hipEventCreate(&e0))) != PS_OK) return rc;
+    if ((rc = hip_status(hipEventCreate(&e1))) != PS_OK) {
+        (void)hipEventDestroy(e0);
+        return rc;
+    }
+    int win = -1;
+    double win_us = 1e300;
+    for (int i = 0; i < n && rc == PS_OK; ++i) {
+        Plan storage;
+        const Plan *pl = nullptr;
+        if ((rc = cached_plan(d, dm, tiles[i], &storage, &pl)) != PS_OK) break;
+        float *ws = pl->ws_need ? (float *)workspace : nullptr;
+        // a few launches to settle, then two timed batches (the second as long as about two milliseconds); the faster counts
+        for (int w = 0; w < 3 && rc == PS_OK; ++w) rc = run_plan(*pl, in_blk, wt_blk, (float *)out_blk, ws, st);
+        int reps = 8;
+        double us = 1e300;
+        for (int batch = 0; batch < 2 && rc == PS_OK; ++batch) {
+            if ((rc = hip_status(hipEventRecord(e0, st))) != PS_OK) break;
+            for (int r = 0; r < reps && rc == PS_OK; ++r) rc = run_plan(*pl, in_blk, wt_blk, (float *)out_blk, ws, st);
+            if (rc != PS_OK || (rc = hip_status(hipEventRecord(e1, st))) != PS_OK) break;
+            if ((rc = hip_status(hipEventSynchronize(e1))) != PS_OK) break;
+            float ms = 0.f;
+            if ((rc = hip_status(hipEventElapsedTime(&ms, e0, e1))) != PS_OK) break;
+            us = std::min(us, (double)ms * 1e3 / reps);
+            reps = std::max(8, std::min(400, (int)(2000.0 / std::max(us, 1.0))));
+        }
+        if (rc == PS_OK && us < win_us) {
+            win_us = us;
+            win = i;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != PS_OK) return rc;
+    if (win < 0) return PS_EUNSUPPORTED;
+    const Pick p{tiles[win], win_us};
+    pick_cache().replace(pick_key(d, dm, 1, ws_bytes), p);
+    if (p.t.c_split == 1) pick_cache().replace(pick_key(d, dm, 0, 0), p);  // the call without a workspace can run it too
+    if (best) *best = p.t;
+    if (best_us) *best_us = win_us;
+    return n;
 }
 
 extern "C" size_t ps_tile_cache_entries(void) { return pick_cache().size() + plan_cache().size(); }

@@ -44,6 +44,11 @@ int hipDeviceGetAttribute(...) { return 100; }
 int hipGetSymbolAddress(...) { return 100; }
 int hipMemcpyAsync(...) { return 100; }
 int hipStreamSynchronize(...) { return 100; }
+int hipEventCreate(...) { return 100; }
+int hipEventDestroy(...) { return 100; }
+int hipEventRecord(...) { return 100; }
+int hipEventSynchronize(...) { return 100; }
+int hipEventElapsedTime(...) { return 100; }
 }
 
 static int g_errors = 0;
@@ -367,6 +372,11 @@ int main()
         const ps_conv_desc d = desc(1, 16, 8, 8, 16, 3, 3, 1, 1, 0);
         alignas(16) static float buf[16 * 64 * 9];
         CHECK(ps_conv2d_fwd_static(&d, nullptr, buf, buf, buf, nullptr) == PS_EHIP && std::strlen(ps_last_hip_error()) > 0, "no-device call");
+        ps_tile t;
+        double us;
+        CHECK(ps_tile_autotune(&d, 3, buf, buf, buf, nullptr, 0, nullptr, &t, &us) == PS_EHIP, "autotune without a device");
+        CHECK(ps_tile_autotune(&d, 0, buf, buf, buf, nullptr, 0, nullptr, &t, &us) == PS_EINVAL, "autotune with k = 0");
+        CHECK(ps_tile_autotune(&d, 3, nullptr, buf, buf, nullptr, 0, nullptr, &t, &us) == PS_EINVAL, "autotune with a null tensor");
     }
     std::printf("host sanitizer driver: %d errors\n", g_errors);
     return g_errors == 0 ? 0 : 1;

@@ -85,3 +85,32 @@ def test_mfma_probe_runs_and_reports_its_flop():
     assert not sink.any()
     with pytest.raises(ps.PsError):
         ps.ps_probe_mfma(7, 100, sink)
+
+
+def test_library_runs_the_top_k_itself_and_keeps_the_winner():
+    """ps_tile_autotune: the k best-ranked tiles are timed on the caller's tensors inside the library, the fastest becomes
+    the descriptor's pick for later calls, and the tensors hold the right result afterwards."""
+    import numpy as np
+    import torch
+    import oracle
+    from gpu_util import DEV, blocked_inputs
+    from paper_2002_02145_amd import binding as ps
+    shape = wl.ConvShape(4, 64, 14, 14, 128, 3, 3, 1, 1, "autotune_3x3_64to128_14")
+    x, w = wl.uniform_pm1(shape, 21)
+    d, xb, wb = blocked_inputs(shape, x, w)
+    ob = torch.full((ps.ps_blocked_out_bytes(d) // 4,), float("nan"), device=DEV)
+    ws = torch.empty((8 << 20) // 4, device=DEV)
+    ranked = [t.as_tuple() for t, _ in ps.ps_tile_rank_ws(d, 8 << 20, 4)]
+    assert ps.ps_tile_pick(d, True, 8 << 20).as_tuple() == ranked[0]
+    tile, us, n = ps.ps_tile_autotune(d, 4, xb, wb, ob, ws, 8 << 20)
+    assert n == 4 and tile.as_tuple() in ranked and 0.5 < us < 1e4
+    assert ps.ps_tile_pick(d, True, 8 << 20).as_tuple() == tile.as_tuple()      # later calls run the winner
+    ob.fill_(float("nan"))
+    ps.ps_conv2d_fwd_ws(d, None, xb, wb, ob, ws, 8 << 20)
+    y = torch.empty((shape.N, shape.K, shape.P, shape.Q), device=DEV)
+    ps.ps_blocked_to_nkpq(d, ob, y)
+    torch.cuda.synchronize()
+    out, mag = oracle.conv2d_fwd(shape, x, w)
+    assert oracle.normalised_error(y.cpu().numpy(), out, mag) <= 1e-4
+    with pytest.raises(ps.PsError):
+        ps.ps_tile_autotune(d, 0, xb, wb, ob, ws, 8 << 20)

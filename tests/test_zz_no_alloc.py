@@ -86,3 +86,54 @@ def test_tile_beyond_the_array_is_refused_and_nothing_runs():
     torch.cuda.synchronize()
     assert ps.ps_workspace_bytes(d, ps.ps_tile_pick(d, True, ps.PS_STATIC_SCRATCH_BYTES)) <= ps.PS_STATIC_SCRATCH_BYTES
     assert not bool(ob.any())
+
+
+def test_static_scratch_calls_replay_from_a_captured_graph():
+    """What the entry point is for: a chain of two convolutions (a split 3x3, then a 1x1 on its output, no transform in
+    between) captured into a HIP graph and replayed.  Capture must find nothing to allocate; every replay, with eager
+    work and synchronisations in between, must reproduce the eager result bit for bit."""
+    from gpu_util import blocked_inputs, DEV
+    s1 = wl.ConvShape(2, 64, 14, 14, 64, 3, 3, 1, 1, "graph_3x3")
+    s2 = wl.ConvShape(2, 64, 14, 14, 128, 1, 1, 1, 0, "graph_1x1")
+    x, w1 = wl.uniform_pm1(s1, 31)
+    _, w2 = wl.uniform_pm1(s2, 32)
+    d1, xb, w1b = blocked_inputs(s1, x, w1)
+    d2, _, w2b = blocked_inputs(s2, np.zeros((s2.N, s2.C, s2.H, s2.W), np.float32), w2)
+    t1 = _split_tile(d1)
+    mid = torch.empty(ps.ps_blocked_out_bytes(d1) // 4, device=DEV)      # blocked output of layer 1 = blocked input of layer 2
+    out = torch.empty(ps.ps_blocked_out_bytes(d2) // 4, device=DEV)
+
+    def chain():
+        ps.ps_conv2d_fwd_static(d1, t1, xb, w1b, mid)
+        ps.ps_conv2d_fwd_static(d2, None, mid, w2b, out)
+
+    chain()                                  # eager: also the first call on the device (looks the array's address up)
+    torch.cuda.synchronize()
+    want_mid, want_out = mid.clone(), out.clone()
+    # against the oracle, layer by layer
+    y1 = torch.empty((s1.N, s1.K, s1.P, s1.Q), device=DEV)
+    ps.ps_blocked_to_nkpq(d1, mid, y1)
+    o1, m1 = oracle.conv2d_fwd(s1, x, w1)
+    assert oracle.normalised_error(y1.cpu().numpy(), o1, m1) <= 1e-4
+    y2 = torch.empty((s2.N, s2.K, s2.P, s2.Q), device=DEV)
+    ps.ps_blocked_to_nkpq(d2, out, y2)
+    o2, m2 = oracle.conv2d_fwd(s2, y1.cpu().numpy(), w2)
+    assert oracle.normalised_error(y2.cpu().numpy(), o2, m2) <= 1e-4
+
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            chain()
+    for replay in range(3):
+        mid.fill_(float("nan"))
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(mid.view(torch.int32), want_mid.view(torch.int32)), f"replay {replay}: first layer differs"
+        assert torch.equal(out.view(torch.int32), want_out.view(torch.int32)), f"replay {replay}: second layer differs"
+        # eager work between replays, on the same scratch array
+        ps.ps_conv2d_fwd_static(d1, t1, xb, w1b, mid)
+        torch.cuda.synchronize()
