@@ -123,7 +123,7 @@ def stored_row(result: dict, N: int) -> dict:
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__)
     ap.add_argument("--layers", default="sweep",
-                    help="sweep (the ResNet-50-shaped set) | heldout | validation (the two out-of-sample sets) | cfg1 | cfg2 | cfg3a | cfg3b | "
+                    help="sweep (the ResNet-50-shaped set) | heldout | validation | first (the out-of-sample sets) | cfg1 | cfg2 | cfg3a | cfg3b | "
                          "comma list of layer names")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--batch", type=int, default=wl.MINIBATCH, help="mini-batch size of the named layer sets")
@@ -140,13 +140,15 @@ def main(argv=None) -> int:
     N = a.batch
     rebatch = lambda L: wl.ConvShape(N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.name)
     named = {"cfg1": wl.CFG1, "cfg2": wl.CFG2, "cfg3a": wl.CFG3A, "cfg3b": wl.CFG3B}
-    named.update({l.name: l for l in wl.resnet50_layers(N) + wl.heldout_layers(N) + wl.validation_layers(N) + [rebatch(wl.CFG3B)]})
+    named.update({l.name: l for l in wl.resnet50_layers(N) + wl.heldout_layers(N) + wl.validation_layers(N) + wl.first_layers(N) + [rebatch(wl.CFG3B)]})
     if a.layers == "sweep":
         layers = wl.resnet50_layers(N) + [rebatch(wl.CFG3B)]
     elif a.layers == "heldout":
         layers = wl.heldout_layers(N)
     elif a.layers == "validation":
         layers = wl.validation_layers(N)
+    elif a.layers == "first":
+        layers = wl.first_layers(N)
     else:
         layers = [named[n] for n in a.layers.split(",")]
     dtype = ps.PS_F32 if a.dtype == "f32" else ps.PS_BF16

@@ -53,9 +53,15 @@ int make_dims(const ps_conv_desc *d, Dims *o)
     return PS_OK;
 }
 
-// 7x7 filter over few input channels (a network stem): the fp32 kernels pack 4 taps x 4 channels into one 16-lane
-// batch element (C <= 4), the 16-bit ones 2 taps x 8 channels (C <= 8).
-bool packs_taps(const Dims &dm) { return dm.C <= (dm.dtype == PS_F32 ? 4 : 8) && dm.R == 7 && dm.S == 7; }
+// Square filter over few input channels (the first layer of an image network): the fp32 kernels pack 4 taps x 4
+// channels into one 16-lane batch element (3x3, 5x5, 7x7, 11x11 over C <= 3; 7x7 also over C = 4), the 16-bit ones
+// 2 taps x 8 channels (the same sides, C <= 8).
+bool packs_taps(const Dims &dm)
+{
+    if (dm.R != dm.S) return false;
+    if (dm.dtype == PS_F32) return packed_side_code(dm.R, dm.C) != 0;
+    return dm.C <= 8 && (dm.R == 3 || dm.R == 5 || dm.R == 7 || dm.R == 11);
+}
 
 const ShapeEntry *find_shape(int dtype, int kt, int mt, int ring)
 {
@@ -97,7 +103,7 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     if (!sh) return PS_EUNSUPPORTED;
     // shapes without a loop for a runtime filter size and without an atomic epilogue: 1x1 and 3x3, unsplit
     if (!sh->launch && !(t.c_split == 1 && ((dm.R == dm.S && (dm.R == 1 || dm.R == 3)) ||
-                                            (packs_taps(dm) && dm.C <= 3 && sh->launch_7x7p))))
+                                            (packs_taps(dm) && dm.C <= 3 && sh->launch_packed))))
         return PS_EUNSUPPORTED;
     // pixel-stationary shapes: 1x1 filters over exactly 4 c-blocks, images of at least 16 pixels
     if (sh->stationary && !(dm.R == 1 && dm.S == 1 && t.c_split == 1 && dm.Cb == 4 && dm.P * dm.Q >= 16))
@@ -133,7 +139,7 @@ int kernel_variant(const Dims &dm, const ps_tile &t, const ShapeEntry &sh)
     const int nb_split = dm.NB / t.c_split;
     if (sh.stationary) return PS_KERNEL_STATIONARY_1X1;  // (tile_valid admits these shapes for nothing else)
     if (sh.launch_halo && halo_applies(dm, t, sh.halo_bytes)) return PS_KERNEL_PATCH_3X3;
-    if (packs_taps(dm) && t.c_split == 1 && sh.launch_7x7p) return PS_KERNEL_PACKED_7X7;
+    if (packs_taps(dm) && t.c_split == 1 && sh.launch_packed) return PS_KERNEL_PACKED_TAPS;
     if (dm.R == dm.S && nb_split % (dm.R * dm.S) == 0) {
         if (dm.R == 1 && sh.launch_1x1) return PS_KERNEL_1X1;
         if (dm.R == 3 && sh.launch_3x3) return PS_KERNEL_3X3;
@@ -192,9 +198,10 @@ int build_plan(const Dims &dm, const ps_tile &t, Plan *pl)
     case PS_KERNEL_STATIONARY_1X1: pl->fn = sh->launch_1x1; break;
     case PS_KERNEL_3X3: pl->fn = sh->launch_3x3; break;
     case PS_KERNEL_PATCH_3X3: pl->fn = sh->launch_halo; break;
-    case PS_KERNEL_PACKED_7X7:
-        pl->fn = sh->launch_7x7p;
-        a.nb_split = dm.dtype == PS_F32 ? 13 : 25;  // 49 taps, four (two) per batch element; a.NB stays 49 for filter addressing
+    case PS_KERNEL_PACKED_TAPS:
+        pl->fn = sh->launch_packed;
+        // four (two) taps per batch element; a.NB stays R * S for filter addressing
+        a.nb_split = dm.dtype == PS_F32 ? (dm.R * dm.S + 3) / 4 : (dm.R * dm.S + 1) / 2;
         break;
     default: break;
     }

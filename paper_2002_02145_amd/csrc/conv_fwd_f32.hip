@@ -5,28 +5,12 @@
 
 namespace ps {
 
-//               KT   MT  WK WM NBUF       wave tile (channels x pixels)
-// Ring depths: a load has (NBUF - 1) iterations to land, and an iteration lasts 512 matrix-core cycles
-// per 32x32 tile a wave owns, so the small wave tiles get the deeper rings.
-#define PS_F32_SHAPE_LIST(X)                                     \
-    X(256, 128, 4, 2, 2) X(256, 128, 4, 2, 4) /* 64 x 64, 8 waves */ \
-    X(256, 64, 4, 1, 2) X(256, 64, 4, 1, 4)   /* 64 x 64 */          \
-    X(128, 128, 2, 2, 2) X(128, 128, 2, 2, 4) /* 64 x 64 */          \
-    X(64, 256, 1, 4, 2) X(64, 256, 1, 4, 4)   /* 64 x 64 */          \
-    X(128, 64, 2, 2, 2) X(128, 64, 2, 2, 4) X(128, 64, 2, 2, 8) /* 64 x 32 */ \
-    X(64, 128, 2, 2, 2) X(64, 128, 2, 2, 4) X(64, 128, 2, 2, 8) /* 32 x 64 */ \
-    X(64, 64, 2, 2, 2) X(64, 64, 2, 2, 4) X(64, 64, 2, 2, 8)    /* 32 x 32 */ \
-    X(128, 32, 4, 1, 4) X(128, 32, 4, 1, 8)   /* 32 x 32 */          \
-    X(32, 128, 1, 4, 4) X(32, 128, 1, 4, 8)   /* 32 x 32 */          \
-    X(64, 32, 2, 1, 4) X(64, 32, 2, 1, 8)     /* 32 x 32, 2 waves */ \
-    X(32, 64, 1, 2, 4) X(32, 64, 1, 2, 8)     /* 32 x 32, 2 waves */
-
 #define PS_TABLE_ROW(KT, MT, WK, WM, NBUF) PS_F32_SHAPE(KT, MT, WK, WM, NBUF),
 static const ShapeEntry kF32Shapes[] = {
     PS_F32_SHAPE_LIST(PS_TABLE_ROW)
     // 64 channels x MT pixels on 16x16x4 MFMA tiles: pixel tiles in steps of 16, for even division over the chip
-    PS_F32_N16_SHAPE(48, 2), PS_F32_N16_SHAPE(48, 4), PS_F32_N16_SHAPE(96, 2), PS_F32_N16_SHAPE(96, 4),
-    PS_F32_N16_SHAPE(176, 2), PS_F32_N16_SHAPE(176, 4),
+#define PS_TABLE_ROW_N16(MT, NBUF) PS_F32_N16_SHAPE(MT, NBUF),
+    PS_F32_N16_SHAPE_LIST(PS_TABLE_ROW_N16)
     PS_F32_N16_KLOOP_SHAPE(48), PS_F32_N16_KLOOP_SHAPE(96), PS_F32_N16_KLOOP_SHAPE(176),
 };
 

@@ -50,12 +50,13 @@ struct N16Shape {
 template <int MT, int NBUF, int SIDE, bool FUSED>
 __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
 {
-    // SIDE = 37: 7x7 filter over at most 3 input channels, tap-packed as in conv_fwd_kernel.h (a batch element holds
-    // 4 consecutive taps x [c0 c1 c2 0]); chunk g of a pixel is then tap g and MFMA step t is channel t, so step 3
-    // would only multiply the padding lane and is left out.
-    static_assert(SIDE == 1 || SIDE == 3 || SIDE == 37, "filter sizes with a baked loop");
-    constexpr bool PACKED = SIDE == 37;
-    constexpr int TAPS = PACKED ? 13 : SIDE * SIDE;
+    // SIDE = 33, 35, 37, 311: F x F filter over at most 3 input channels, tap-packed as in conv_fwd_kernel.h (a batch
+    // element holds 4 consecutive taps x [c0 c1 c2 0]); chunk g of a pixel is then tap g and MFMA step t is channel t,
+    // so step 3 would only multiply the padding lane and is left out.
+    static_assert(SIDE == 1 || SIDE == 3 || (side_packs(SIDE) && side_skips_c3(SIDE)), "filter sizes with a baked loop");
+    constexpr bool PACKED = side_packs(SIDE);
+    constexpr int FS = side_filter(SIDE);
+    constexpr int TAPS = PACKED ? (FS * FS + 3) / 4 : SIDE * SIDE;
     constexpr int STEPS = PACKED ? 3 : 4;
     using Sh = N16Shape<MT, NBUF, FUSED>;
     constexpr int NW = Sh::NW, NT = Sh::NT, APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
@@ -92,11 +93,11 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
 #define PS_N16_TAP_OFFSETS(T0_, T1_)                                                                        \
     _Pragma("unroll") for (int i = 0; i < APW; ++i)                                                        \
         _Pragma("unroll") for (int t = (T0_); t < (T1_); ++t) {                                            \
-            /* packed: this lane fetches channels 0..3 of tap 4t + lane%4 of the sequence r*7 + s (x*37 >> 8 = x/7) */ \
+            /* packed: this lane fetches channels 0..3 of tap 4t + lane%4 of the sequence r*F + s */          \
             const int tapidx = 4 * t + (lane & 3);                                                         \
-            const int r = PACKED ? (tapidx * 37) >> 8 : t / SIDE, sx = PACKED ? tapidx - 7 * r : t % SIDE; \
+            const int r = PACKED ? tapidx / FS : t / FS, sx = PACKED ? tapidx - FS * r : t % FS;           \
             const bool ok = ((unsigned)(ph0[i] + r) < (unsigned)a.H) & ((unsigned)(pw0[i] + sx) < (unsigned)a.W) & \
-                            (!PACKED || tapidx < 49);                                                      \
+                            (!PACKED || tapidx < FS * FS);                                                 \
             vtap[i][t] = ok ? (unsigned)((ppoff[i] + r * a.W + sx) * 64 + (PACKED ? 0 : (lane & 3) * 16)) : kOobOffset; \
         }
     constexpr int FIRST_TAPS = D < TAPS ? D : TAPS;
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     // adjacent 64-byte rows (all banks) instead of rows 256 bytes apart (one bank group, four-way conflict).
     const unsigned wsrc = (unsigned)((4 * ((lane >> 2) & 3) + (lane >> 4)) * 64 + (lane & 3) * 16);
     // packed: position (t, g, q) takes row t (channel) of the block of tap 4e + g; channel 3 is never multiplied;
-    // [1] is for the last element, where only tap 48 exists
+    // [1] is for the last element, where only the last tap exists
     const unsigned wpk = (lane >> 4) == 3 ? kOobOffset : (unsigned)(((lane >> 2) & 3) * 1024 + (lane >> 4) * 64 + (lane & 3) * 16);
     const unsigned vw[2] = {PACKED ? wpk : wsrc, PACKED ? (((lane >> 2) & 3) == 0 ? wpk : kOobOffset) : wsrc};
 
@@ -282,10 +283,16 @@ void launch_f32_n16(const ConvArgs &a, unsigned grid, hipStream_t st)
         hipLaunchKernelGGL((conv_fwd_f32_n16_kernel<MT, NBUF, SIDE, false>), dim3(grid), dim3(256), 0, st, a);
 }
 
+// the tap-packed kernels of a shape, chosen by the filter side of the arguments (defined and instantiated in
+// conv_fwd_f32_packed.hip)
+template <int MT, int NBUF>
+void launch_f32_n16_packed(const ConvArgs &a, unsigned grid, hipStream_t st);
+
 // No loop with a runtime filter size and no atomic epilogue: the enumerator offers these shapes for 1x1 and 3x3
-// filters and for 7x7 filters over at most 3 channels, unsplit.
+// filters and for the tap-packed filters over at most 3 channels, unsplit.
 #define PS_F32_N16_SHAPE(MT, NBUF)                                                                  \
     {PS_F32, 64, MT, NBUF, 256, N16Shape<MT, NBUF>::LDS_BYTES, 1, nullptr, &launch_f32_n16<MT, NBUF, 1>, \
-     &launch_f32_n16<MT, NBUF, 3>, &launch_f32_n16<MT, NBUF, 37>, nullptr, 0}
+     &launch_f32_n16<MT, NBUF, 3>, &launch_f32_n16_packed<MT, NBUF>, nullptr, 0}
+#define PS_F32_N16_SHAPE_LIST(X) X(48, 2) X(48, 4) X(96, 2) X(96, 4) X(176, 2) X(176, 4)
 
 }  // namespace ps

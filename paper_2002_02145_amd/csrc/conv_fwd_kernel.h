@@ -333,6 +333,22 @@ __device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, con
 
 constexpr int ct_gcd(int x, int y) { return y == 0 ? x : ct_gcd(y, x % y); }
 
+// Codes of the loops with the filter baked in (template argument SIDE of the fp32 kernels):
+//   1, 3        R = S = SIDE, 16 channels of one tap per batch element;
+//   7           tap-packed 7x7 over at most 4 input channels (4 taps x 4 channels per batch element);
+//   30 + F      tap-packed F x F over at most 3 input channels, F = 3, 5, 7 (the zero fourth lane is never multiplied);
+//   311         the same for 11 x 11.
+constexpr bool side_packs(int side) { return side == 7 || side >= 30; }
+constexpr bool side_skips_c3(int side) { return side >= 30; }
+constexpr int side_filter(int side) { return side >= 300 ? side - 300 : side >= 30 ? side - 30 : side; }
+// the code for an F x F filter over `cin` input channels, 0 if that combination has no tap-packed loop
+inline int packed_side_code(int F, int cin)
+{
+    if (F == 7 && cin == 4) return 7;
+    if (cin > 3) return 0;
+    return F == 3 || F == 5 || F == 7 ? 30 + F : F == 11 ? 311 : 0;
+}
+
 // SIDE > 0 bakes a square SIDE x SIDE filter into the loop (R = S = SIDE, split ranges on c-block
 // boundaries): every load's per-lane offset, validity included, is then precomputed per tap, and the loop
 // issues no vector-ALU instruction at all.  That matters because on this hardware each VALU instruction
@@ -341,18 +357,20 @@ constexpr int ct_gcd(int x, int y) { return y == 0 ? x : ct_gcd(y, x % y); }
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
 __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvArgs a)
 {
-    // SIDE = 7 is the tap-packed mode for inputs with at most 4 channels (one c-block whose lanes 4..15 are
-    // zero padding, e.g. an RGB network stem): a batch element then holds channels 0..3 of four horizontally
+    // Tap-packed mode (codes above) for inputs with at most 4 channels (one c-block whose lanes 4..15 are
+    // zero padding, e.g. an RGB network stem): a batch element then holds channels 0..3 of four
     // consecutive taps of the row-major tap sequence (4 taps x 4 channels = the 16 reduction lanes) instead of 16
-    // channels of one tap, so a 7x7 filter takes ceil(49 / 4) = 13 elements instead of 49.  Pixels and filter blocks
-    // are gathered accordingly from the ordinary blocked tensors: only the per-lane load offsets differ.
-    constexpr bool PACK4 = SIDE == 7 || SIDE == 37;
-    // SIDE = 37: the same with at most 3 input channels.  Lane 3 of every tap's 4-channel group is then zero padding,
-    // and with the reduction index permuted as below it is MFMA steps 3 and 7 that would multiply it: they are
-    // left out, a quarter of the matrix-core work.
-    constexpr bool SKIP_C3 = SIDE == 37;
-    constexpr int FS = PACK4 ? 7 : SIDE;  // filter side
-    constexpr int TAPS = PACK4 ? 13 : SIDE * SIDE;
+    // channels of one tap, so a 7x7 filter takes ceil(49 / 4) = 13 elements instead of 49, an 11x11 one 31 instead of
+    // 121.  Pixels and filter blocks are gathered accordingly from the ordinary blocked tensors: only the per-lane load
+    // offsets differ.  (F * F is odd for every F offered, so the last element always holds exactly one tap.)
+    constexpr bool PACK4 = side_packs(SIDE);
+    // With at most 3 input channels lane 3 of every tap's 4-channel group is zero padding, and with the reduction
+    // index permuted as below it is MFMA steps 3 and 7 that would multiply it: they are left out, a quarter of the
+    // matrix-core work.
+    constexpr bool SKIP_C3 = side_skips_c3(SIDE);
+    constexpr int FS = side_filter(SIDE);  // filter side
+    constexpr int FSD = FS > 0 ? FS : 1;
+    constexpr int TAPS = PACK4 ? (FS * FS + 3) / 4 : SIDE * SIDE;
     using Sh = F32Shape<KT, MT, WK, WM, NBUF>;
     constexpr int NW = Sh::NW, TK = Sh::TK, TM = Sh::TM;
     constexpr int APW = Sh::APW, WPW = Sh::WPW, LPE = Sh::LPE, D = Sh::D;
@@ -443,13 +461,13 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 #pragma unroll
             for (int t = 0; t < TAPS; ++t) {
                 // ordinary: tap (r, sx), this lane fetches chunk `gchunk` of the pixel's 16 channels;
-                // tap-packed: element t holds taps 4t .. 4t+3 of the sequence r*7 + s, this lane fetches channels
-                // 0..3 of tap 4t + gchunk (x * 37 >> 8 = x / 7 for x < 56)
+                // tap-packed: element t holds taps 4t .. 4t+3 of the sequence r*F + s, this lane fetches channels
+                // 0..3 of tap 4t + gchunk
                 const int tapidx = 4 * t + gchunk;
-                const int r = PACK4 ? (tapidx * 37) >> 8 : t / FS;
-                const int sx = PACK4 ? tapidx - 7 * r : t % FS;
+                const int r = PACK4 ? tapidx / FSD : t / FSD;
+                const int sx = PACK4 ? tapidx - FS * r : t % FSD;
                 const bool ok = ((unsigned)(h0[i] + r) < (unsigned)a.H) & ((unsigned)(w0[i] + sx) < (unsigned)a.W) &
-                                (!PACK4 || tapidx < 49);
+                                (!PACK4 || tapidx < FS * FS);
                 vtap[i][t] = ok ? (unsigned)((poff[i] + r * a.W + sx) * 64 + (PACK4 ? 0 : gchunk * 16)) : kOobOffset;
             }
 #pragma unroll
@@ -461,7 +479,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
     }
     // per-lane offset of a filter load inside its 1 KB block: lane*16 normally; tap-packed, LDS row
     // c' = lane/4 = 4*j + c is row c of the block of tap 4t + j (blocks follow the tap sequence; [1]: the last
-    // element, where only tap 48 exists)
+    // element, where only the last tap exists)
     unsigned vw[2];
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
@@ -589,7 +607,7 @@ struct ShapeEntry {
     LaunchFn launch;      // any filter size
     LaunchFn launch_1x1;  // R = S = 1 baked in (nullptr if not compiled)
     LaunchFn launch_3x3;  // R = S = 3 baked in
-    LaunchFn launch_7x7p; // R = S = 7, C <= 4: tap-packed
+    LaunchFn launch_packed; // tap-packed loops (R = S = 3, 5, 7, 11 over at most 3 channels; 7x7 over 4), by the arguments
     LaunchFn launch_halo; // 3x3, stride 1, pad 1 with the input patch staged once per c-block (nullptr if none)
     int halo_bytes;       // capacity of that kernel's patch
     int stationary;       // 1: pixels with all their input channels stay in LDS (1x1 filters, C = 64 only)
@@ -603,19 +621,31 @@ void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
     hipLaunchKernelGGL((conv_fwd_f32_kernel<KT, MT, WK, WM, NBUF, SIDE>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
 
-// tap-packed 7x7: with at most 3 real input channels the kernel that leaves out the zero lane's MFMA steps
+// the tap-packed kernels of a shape, chosen by filter side and channel count of the arguments (defined and
+// instantiated in conv_fwd_f32_packed.hip)
 template <int KT, int MT, int WK, int WM, int NBUF>
-void launch_f32_packed(const ConvArgs &a, unsigned grid, hipStream_t st)
-{
-    if (a.cin <= 3)
-        launch_f32<KT, MT, WK, WM, NBUF, 37>(a, grid, st);
-    else
-        launch_f32<KT, MT, WK, WM, NBUF, 7>(a, grid, st);
-}
+void launch_f32_packed(const ConvArgs &a, unsigned grid, hipStream_t st);
 
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
     {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES, 1,                   \
      &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
      &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32_packed<KT, MT, WK, WM, NBUF>, nullptr, 0}
+
+//               KT   MT  WK WM NBUF       wave tile (channels x pixels)
+// Ring depths: a load has (NBUF - 1) iterations to land, and an iteration lasts 512 matrix-core cycles
+// per 32x32 tile a wave owns, so the small wave tiles get the deeper rings.
+#define PS_F32_SHAPE_LIST(X)                                     \
+    X(256, 128, 4, 2, 2) X(256, 128, 4, 2, 4) /* 64 x 64, 8 waves */ \
+    X(256, 64, 4, 1, 2) X(256, 64, 4, 1, 4)   /* 64 x 64 */          \
+    X(128, 128, 2, 2, 2) X(128, 128, 2, 2, 4) /* 64 x 64 */          \
+    X(64, 256, 1, 4, 2) X(64, 256, 1, 4, 4)   /* 64 x 64 */          \
+    X(128, 64, 2, 2, 2) X(128, 64, 2, 2, 4) X(128, 64, 2, 2, 8) /* 64 x 32 */ \
+    X(64, 128, 2, 2, 2) X(64, 128, 2, 2, 4) X(64, 128, 2, 2, 8) /* 32 x 64 */ \
+    X(64, 64, 2, 2, 2) X(64, 64, 2, 2, 4) X(64, 64, 2, 2, 8)    /* 32 x 32 */ \
+    X(128, 32, 4, 1, 4) X(128, 32, 4, 1, 8)   /* 32 x 32 */          \
+    X(32, 128, 1, 4, 4) X(32, 128, 1, 4, 8)   /* 32 x 32 */          \
+    X(64, 32, 2, 1, 4) X(64, 32, 2, 1, 8)     /* 32 x 32, 2 waves */ \
+    X(32, 64, 1, 2, 4) X(32, 64, 1, 2, 8)     /* 32 x 32, 2 waves */
+
 
 }  // namespace ps

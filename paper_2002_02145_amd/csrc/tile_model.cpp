@@ -78,27 +78,32 @@ bool stationary_applies(const Dims &dm)
     return dm.dtype == PS_F32 && dm.R == 1 && dm.S == 1 && dm.Cb == 4 && (long long)dm.P * dm.Q >= 16;
 }
 
+// The tap-packed loop runs: an unsplit range of a layer it exists for, unless the 16-bit patch loop takes the tile.
+bool packed_runs(const Dims &dm, int nb_split, bool patch) { return packs_taps(dm) && nb_split == dm.NB && !patch; }
+
 // batch elements one loop iteration of the kernel consumes (the 16-bit kernels group several per ring slot;
 // their 3x3 variant takes one filter row)
-int group_of(const Dims &dm, const ShapeInfo &sh, int nb_split)
+int group_of(const Dims &dm, const ShapeInfo &sh, int nb_split, bool patch = false)
 {
     if (dm.dtype == PS_F32) return 1;
+    if (packed_runs(dm, nb_split, patch)) return sh.group;
     return baked_filter(dm, nb_split) && dm.R == 3 ? 3 : sh.group;  // (the patch kernel: see model_cost)
 }
 
 // batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples
 
-int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
+int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split, bool patch = false)
 {
     const int ring = sh.ring;
     int unit = ring;
     if (dm.dtype != PS_F32) {
-        const int g = group_of(dm, sh, nb_split);
-        if (packs_taps(dm) && baked_filter(dm, nb_split)) return (25 + g - 1) / g * g;  // 25 tap-packed elements, g per iteration
+        const int g = group_of(dm, sh, nb_split, patch);
+        // tap-packed: two taps per element, g elements per iteration
+        if (packed_runs(dm, nb_split, patch)) return ((dm.R * dm.S + 1) / 2 + g - 1) / g * g;
         unit = ring * g;
         if (g == 3) unit = ring % 3 == 0 ? ring * 3 : ring * 9;  // lcm(ring, 3) iterations of 3 elements
     } else if (baked_filter(dm, nb_split)) {
-        if (packs_taps(dm)) return 13;  // 49 taps, four per element, in one pass of exactly 13 iterations
+        if (packs_taps(dm)) return (dm.R * dm.S + 3) / 4;  // four taps per element, in one pass of exactly that many iterations
         const int taps = dm.R * dm.S;
         int g = ring, h = taps;
         while (h) { const int r = g % h; g = h; h = r; }
@@ -107,11 +112,11 @@ int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
     return (nb_split + unit - 1) / unit * unit;
 }
 
-// batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples: the tap-packed loops
-// run their 13 elements (in whole iterations) whatever the ring depth
-int logical_elems(const Dims &dm, const ShapeInfo &sh, int nb_split)
+// batch elements the range holds as the kernel counts them: the tap-packed loops run their elements (in whole
+// iterations) whatever the ring depth
+int logical_elems(const Dims &dm, const ShapeInfo &sh, int nb_split, bool patch = false)
 {
-    return baked_filter(dm, nb_split) && packs_taps(dm) ? padded_elems(dm, sh, nb_split) : nb_split;
+    return packed_runs(dm, nb_split, patch) ? padded_elems(dm, sh, nb_split, patch) : nb_split;
 }
 
 // Working sets of the tile's data reuses, and the level each one is served from (the analogue of
@@ -129,13 +134,14 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double n_mt = std::ceil(M / t.mt), n_kt = std::ceil((double)dm.K / t.kt);
     const double nwg = n_mt * n_kt * t.c_split;
     const double nb_split = (double)dm.NB / t.c_split;
-    const double nb_pad = padded_elems(dm, sh, dm.NB / t.c_split);  // zero elements pad the range
-    const bool baked = baked_filter(dm, dm.NB / t.c_split);
-    const double es = dm.es;
-    const double waves_wg = sh.threads / 64.0;
     // 16-bit 3x3 / stride 1 / pad 1: the ring-2 rows of a shape run the kernel that stages the input patch once per
     // c-block (two slots of one c-block each) instead of gathering every tap
     const bool patch = sh.halo_bytes > 0 && halo_applies(dm, t, sh.halo_bytes);
+    const bool packed = packed_runs(dm, dm.NB / t.c_split, patch);
+    const double nb_pad = padded_elems(dm, sh, dm.NB / t.c_split, patch);  // zero elements pad the range
+    const bool baked = baked_filter(dm, dm.NB / t.c_split);
+    const double es = dm.es;
+    const double waves_wg = sh.threads / 64.0;
 
     // ---- residency --------------------------------------------------------------------------------
     const double tiles_wave = (double)t.kt * t.mt / (waves_wg * 1024.0);  // 32x32 MFMA tiles per wave
@@ -146,7 +152,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     double lds_used = sh.lds_bytes;
     if (patch && sh.lds_halo > 0)
         lds_used = sh.lds_halo;
-    else if (dm.dtype != PS_F32 && baked && dm.R == 3 && sh.lds_3x3 > 0)
+    else if (dm.dtype != PS_F32 && baked && dm.R == 3 && !packed && sh.lds_3x3 > 0)
         lds_used = sh.lds_3x3;
     double occ = std::floor(c.lds_bytes / lds_used);
     occ = std::max(1.0, std::min(occ, std::floor(waves_simd * 4.0 / waves_wg)));
@@ -167,13 +173,13 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     }
     const double mfma_clk = dm.dtype == PS_F32 ? 64.0 * 8.0 : 32.0;  // per 32x32 tile per batch element
     const double eff = baked ? c.steady_eff_baked : c.steady_eff_general[dm.dtype == PS_F32 ? 0 : 1];
-    // tap-packed 7x7 over at most 3 channels: the MFMA steps of the zero lane are left out
-    const double lane_skip = dm.dtype == PS_F32 && packs_taps(dm) && baked && dm.C <= 3 ? 0.75 : 1.0;
+    // tap-packed over at most 3 channels: the MFMA steps of the zero lane are left out
+    const double lane_skip = dm.dtype == PS_F32 && packed && dm.C <= 3 ? 0.75 : 1.0;
     const double clk_wave = tiles_wave * mfma_clk * lane_skip * nb_pad / eff;
     // per batch element a wave also pays a barrier and the issue of its loads and LDS reads; with a
     // single resident wave per SIMD nothing hides that
     const double waves_res = std::min(per_simd, std::max(1.0, std::floor(occ * waves_wg / 4.0)));
-    const double grp = patch ? 9.0 : group_of(dm, sh, dm.NB / t.c_split);  // batch elements per loop iteration
+    const double grp = patch ? 9.0 : group_of(dm, sh, dm.NB / t.c_split, patch);  // batch elements per loop iteration
     const double n_iter = nb_pad / grp;
     // (a lone 16-bit wave cannot hide its barrier behind its own short MFMA stream; an fp32 one can)
     const bool f32 = dm.dtype == PS_F32;
@@ -188,7 +194,17 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const double in_b0 = (double)dm.N * dm.Cb * dm.H * dm.W * 16.0 * dm.es;
     const double wt_b0 = (double)dm.Kb * 16.0 * dm.Cb * 16.0 * dm.R * dm.S * dm.es;
     const bool l2_resident = (in_b0 + M * dm.K * 4.0) / c.xcds + wt_b0 <= c.l2_bytes;
-    const double latency = f32 && l2_resident ? c.l2_hit_latency_clk : c.load_latency_clk;
+    double latency = f32 && l2_resident ? c.l2_hit_latency_clk : c.load_latency_clk;
+    if (packed) {
+        // A tap-packed gather uses 16 bytes of every pixel it touches, so one load instruction (1 KB into LDS) passes
+        // more 64-byte lines through the unit's L1, which takes one line per clock, than the 16 of an ordinary load:
+        // the input pixels between its first and last (pixel, tap), i.e. up to 64 at stride 4.  The loads of one batch
+        // element from all resident workgroups queue there, and what the queue takes beyond fully used lines is
+        // latency the ring has to cover.
+        const double px_instr = f32 ? 16.0 : 32.0, taps_instr = f32 ? 4.0 : 2.0, px_line = f32 ? 1.0 : 2.0;
+        const double lines = std::min(64.0, ((px_instr - 1.0) * dm.stride + taps_instr) / px_line);
+        latency += std::min(occ, per_cu) * std::max(0.0, lines - 16.0) * (t.mt / px_instr);
+    }
     const double cover = (t.ring - 1) * clk_iter / latency;
     const double stall = std::max(0.0, latency / (t.ring - 1) - clk_iter) + (f32 ? 0.10 : 0.50) * clk_iter * std::exp(-cover);
     if (patch) {

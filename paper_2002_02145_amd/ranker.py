@@ -91,7 +91,7 @@ def tile_stats(desc: ps.ConvDesc, kind: int, workspace_bytes: int = 1 << 62, til
 
 
 def _named_layers(N: int):
-    named = {l.name: l for l in wl.resnet50_layers(N) + wl.heldout_layers(N) + wl.validation_layers(N)}
+    named = {l.name: l for l in wl.resnet50_layers(N) + wl.heldout_layers(N) + wl.validation_layers(N) + wl.first_layers(N)}
     b = wl.CFG3B
     named[b.name] = wl.ConvShape(N, b.C, b.H, b.W, b.K, b.R, b.S, b.stride, b.pad, b.name)
     return named

@@ -119,6 +119,20 @@ def validation_layers(N: int = MINIBATCH) -> list[ConvShape]:
     ]
 
 
+def first_layers(N: int = MINIBATCH) -> list[ConvShape]:
+    """First layers of image networks of the kinds Section 5.1 lists: three input channels, 3x3 filters with stride 1
+    or 2 at 224 to 416 pixels, 11x11 with stride 4.  The paper leaves such layers out (channel counts that are not
+    multiples of 16); here the tap-packed loops run them.  Synthetic stand-ins chosen here; nothing in the tile model was
+    ever adjusted on them."""
+    return [
+        ConvShape(N, 3, 299, 299, 32, 3, 3, 2, 0, "3x3s2_3to32_299"),
+        ConvShape(N, 3, 224, 224, 32, 3, 3, 2, 1, "3x3s2_3to32_224"),
+        ConvShape(N, 3, 224, 224, 64, 3, 3, 1, 1, "3x3_3to64_224"),
+        ConvShape(N, 3, 416, 416, 32, 3, 3, 1, 1, "3x3_3to32_416"),
+        ConvShape(N, 3, 227, 227, 96, 11, 11, 4, 0, "11x11s4_3to96_227"),
+    ]
+
+
 def sweep_seed(layer_index: int) -> int:
     return 100 + layer_index
 

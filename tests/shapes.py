@@ -21,4 +21,12 @@ EDGE_SHAPES = [
     ConvShape(1, 64, 5, 5, 240, 1, 1, 1, 1, "1x1_64to240_pad1"),        # ... last channel block missing, padded border
     ConvShape(2, 3, 18, 15, 128, 7, 7, 2, 3, "stem_like_K128"),         # tap-packed 7x7 on the wide channel tiles
     ConvShape(1, 7, 11, 12, 96, 7, 7, 1, 3, "7x7_C7_K96"),              # 16-bit packing uses 8 channel lanes; K = 96 pads a 64-wide tile
+    # tap-packed loops of the other filter sides (first layers of image networks)
+    ConvShape(2, 3, 13, 11, 32, 3, 3, 2, 1, "3x3s2_C3_K32"),            # 9 taps: 3 (fp32) / 5 (16-bit) batch elements
+    ConvShape(2, 3, 9, 12, 64, 3, 3, 1, 1, "3x3s1p1_C3_K64"),           # 16-bit: the patch loop has first call here
+    ConvShape(1, 2, 12, 10, 48, 5, 5, 1, 2, "5x5_C2_K48"),
+    ConvShape(2, 3, 35, 31, 64, 11, 11, 4, 2, "11x11s4_C3_K64"),        # 121 taps: 31 / 61 batch elements
+    ConvShape(1, 3, 27, 23, 96, 11, 11, 4, 0, "11x11s4_C3_K96_nopad"),
+    ConvShape(1, 6, 10, 9, 32, 5, 5, 2, 2, "5x5_C6_K32"),               # packed in 16 bits only
+    ConvShape(1, 4, 8, 8, 16, 3, 3, 1, 1, "3x3_C4_fp32_not_packed"),    # four channels: only 7x7 packs them in fp32
 ]

@@ -128,10 +128,10 @@ def test_resnet50_sweep(dtype):
 
 @pytest.mark.parametrize("dtype", [0, 1], ids=["fp32", "bf16"])
 def test_out_of_sample_layer_sets(dtype):
-    """The layers of the two out-of-sample sets (other widths, 5x5 and 11x11 filters, strided 3x3, a 96-channel stem)
-    at N = 28 with the library's pick: every output element against the oracle."""
+    """The layers of the out-of-sample sets (other widths, 5x5 and 11x11 filters, strided 3x3, a 96-channel stem, first
+    layers with three input channels) at N = 28 with the library's pick: every output element against the oracle."""
     from gpu_util import run_conv
-    for i, shape in enumerate(wl.heldout_layers() + wl.validation_layers()):
+    for i, shape in enumerate(wl.heldout_layers() + wl.validation_layers() + wl.first_layers()):
         x, w = _prep(shape, wl.relu_like, 200 + i, dtype)
         got = run_conv(shape, x, w, dtype, ws=True)
         out, mag = oracle.conv2d_fwd(shape, x, w)
