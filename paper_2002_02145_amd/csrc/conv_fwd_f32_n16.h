@@ -201,10 +201,10 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
         }                                                                                                  \
         if (bf16_out) {                                                                                    \
             const uintx2_t h_ = {pack_bf16(v_[0], v_[1]), pack_bf16(v_[2], v_[3])};                        \
-            __builtin_amdgcn_raw_buffer_store_b64(h_, rout, VOFF_, SOFF_, 0);                              \
+            __builtin_amdgcn_raw_buffer_store_b64(h_, rout, VOFF_, SOFF_, kStoreWholeLines);               \
         } else {                                                                                           \
             const uintx4_t u_ = __builtin_bit_cast(uintx4_t, v_);                                          \
-            __builtin_amdgcn_raw_buffer_store_b128(u_, rout, VOFF_, SOFF_, 0);                             \
+            __builtin_amdgcn_raw_buffer_store_b128(u_, rout, VOFF_, SOFF_, kStoreWholeLines);              \
             /* keep the four stored registers live across a short pause: a vector-ALU result allocated */  \
             /* into them right after the store could overtake the store's read of them (see write_out) */  \
             asm volatile("s_nop 1" ::"v"(u_));                                                             \
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
         unsigned voff = l16 >= a.PQ - r ? vnext : vlane;                                                   \
         if (!(FULL_)) voff = l16 < a.M - m0 - j * 16 ? voff : kOobOffset;                                  \
         if constexpr (PLAIN_) {                                                                            \
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff, S, 0); \
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff, S, kStoreWholeLines); \
         } else {                                                                                           \
             PS_N16_FUSED_STORE(acc[j], voff, S)                                                            \
         }                                                                                                  \
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
             if constexpr (FUSED) {
                 PS_N16_FUSED_STORE(acc[j], voff, soff)
             } else {
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff, soff, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff, soff, kStoreWholeLines);
             }
         }
     }

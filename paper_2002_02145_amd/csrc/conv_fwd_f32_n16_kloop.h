@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kloop_kernel(const ConvA
             for (int j = 0; j < NT; ++j) {
                 if constexpr (!FUSED) {
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, acc[j]), rout, voff[j],
-                                                           soff[j] + kstep, 0);
+                                                           soff[j] + kstep, kStoreWholeLines);
                 } else {
                     floatx4_n v = acc[j] + bias[J];
                     if (epi & 2) {
@@ -225,10 +225,10 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kloop_kernel(const ConvA
                     }
                     if (bf16_out) {
                         const uintx2_t h = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                        __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff[j], soff[j] + kstep, 0);
+                        __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff[j], soff[j] + kstep, kStoreWholeLines);
                     } else {
                         const uintx4_t u = __builtin_bit_cast(uintx4_t, v);
-                        __builtin_amdgcn_raw_buffer_store_b128(u, rout, voff[j], soff[j] + kstep, 0);
+                        __builtin_amdgcn_raw_buffer_store_b128(u, rout, voff[j], soff[j] + kstep, kStoreWholeLines);
                         asm volatile("s_nop 1" ::"v"(u));  // store-data guard, see conv_fwd_f32_n16.h
                     }
                 }

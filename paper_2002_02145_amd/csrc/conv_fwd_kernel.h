@@ -38,6 +38,7 @@
 //   * Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id is remapped so
 //     that each XCD works on a contiguous run of tiles and neighbouring tiles share its L2.
 #pragma once
+#include <type_traits>
 #include "ps_internal.h"
 
 namespace ps {
@@ -148,6 +149,16 @@ __device__ inline unsigned bf16_bits_rne(float x)
 }
 __device__ inline unsigned pack_bf16(float lo, float hi) { return bf16_bits_rne(lo) | (bf16_bits_rne(hi) << 16); }
 
+// Cache policy (auxiliary operand of the buffer-store builtins; bit 4 = sc1) of output stores whose every instruction
+// covers whole 64-byte lines, as in the 16x16-tile kernels: the line is written through L2 at once instead of
+// staying there dirty until it is evicted, which leaves the L2 to the operands.  Measured at N = 28: 3x3 64 -> 64 at
+// 56x56 48.9 -> 47.2 us, the pixel-stationary 1x1 64 -> 256 27.8 -> 24.2 us, 1x1 256 -> 64 25.8 -> 25.6 us; the
+// non-temporal hint (bit 1) gives the same on the first and less on the second.  It only pays for whole lines: half
+// lines written through one by one no longer merge in L2 and everything gets slower (16-bit stem 39 -> 47 us, 16-bit
+// 1x1 64 -> 256 21 -> 37 us with the 32x32-tile kernels' stores as the accumulator layout has them), which is why
+// write_out below turns its tiles around first.
+constexpr int kStoreWholeLines = 16;
+
 // Epilogue shared by the fp32 and bf16 kernels: accumulators -> out[n][kb][p][q][16 k].
 // acc[tk][tm] is the 32x32 tile (output channels x pixels) number (tk, tm) of this wave in the MFMA
 // result layout: register r of lane l holds channel 8*(r/4) + 4*(l/32) + r%4 of pixel l%32.
@@ -157,79 +168,85 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
 {
     const int wk = wave % WK, wm = wave / WK;
     const int half = lane >> 5, l32 = lane & 31;
+    float *const stage = reinterpret_cast<float *>(lds) + wave * (32 * EPITCH);  // this wave's 32x32 patch
+    const int rp = lane >> 3, c4 = lane & 7;
     if (a.c_split == 1 || a.partial != nullptr) {
-        // A lane holds one pixel and 4 consecutive channels per register quad: one 16-byte store each.
+        // From the accumulator layout a store instruction would write 32 bytes of each of 32 pixels: half a 64-byte
+        // line, the other half following with the next instruction.  Each wave therefore turns its 32x32 tile around
+        // in a private LDS patch, so that 4 consecutive lanes cover one pixel's 16-channel line (lanes 4..7 of the
+        // group: the next channel block's) and an instruction writes 16 whole lines, with the write-through policy
+        // that whole lines allow (kStoreWholeLines).  Measured at N = 28 with 16-bit inputs: 3x3 64 -> 64 at 56x56
+        // 14.4 -> 11.5 us, 1x1 64 -> 256 21.4 -> 17.1 us, 1x1 128 -> 512 14.3 -> 11.1 us; same bits.
         // With a workspace, split s stores its partial tile into plane s; a second kernel adds the planes.
         // Buffer stores: the per-lane part of the address (pixel, channel quad) is computed once per pixel
-        // tile, the channel-block part is a scalar offset, and lanes past the end of the tensor get an
+        // tile, the tile's channel-block part is a scalar offset, and lanes past the end of the tensor get an
         // out-of-range offset, which drops their store.
         float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
         const int epi = a.c_split == 1 ? a.epi : 0;  // a split's partial planes stay raw; the adding pass applies it
-        if (epi == 0) {
-            // plain store straight from the accumulator registers, which nothing overwrites afterwards
-            const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, a.out_bytes);
-            const int kb_stride = a.PQ * 64;  // bytes from one 16-channel block plane to the next
+        wait_vm_and_barrier<0>();  // every wave has read its last fragments: the ring may be overwritten
+        // Two instances of the loop: the plain one has no branch between the LDS reads and the stores of a tile, so
+        // the four reads are issued together and the stores follow as the data return.
+        auto store_tiles = [&](auto fused_tag) {
+            constexpr bool FUSED = decltype(fused_tag)::value;
+            const bool bf16_out = FUSED && (epi & 4);
+            const int esz = bf16_out ? 2 : 4;
+            const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, bf16_out ? a.out_bytes / 2 : a.out_bytes);
+            const int plane = a.PQ * 16 * esz;  // bytes from one 16-channel block plane to the next
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                const int m = m0 + (wm * TM + tm) * 32 + l32;
-                int n, pq;
-                fast_divmod(m, a.PQ, a.magic_pq, n, pq);
-                const unsigned voff = m < a.M ? (unsigned)((n * a.Kb * a.PQ + pq) * 64 + half * 16) : kOobOffset;
+                unsigned vpix[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int m = m0 + (wm * TM + tm) * 32 + rp + 8 * i;
+                    int n, pq;
+                    fast_divmod(m, a.PQ, a.magic_pq, n, pq);
+                    vpix[i] = m < a.M ? (unsigned)(((n * a.Kb * a.PQ + pq) * 16 + (c4 & 3) * 4) * esz + (c4 >> 2) * plane) : kOobOffset;
+                }
 #pragma unroll
                 for (int tk = 0; tk < TK; ++tk) {
 #pragma unroll
                     for (int rq = 0; rq < 4; ++rq) {
-                        const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8;  // uniform; this lane: + half*4
-                        if (ofm0 >= a.Kb * 16) continue;  // K not a multiple of the tile: padded channels are dropped
                         const floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
                                            acc[tk][tm][rq * 4 + 3]};
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff,
-                                                               (ofm0 >> 4) * kb_stride + (ofm0 & 15) * 4, 0);
+                        *reinterpret_cast<floatx4 *>(stage + l32 * EPITCH + rq * 8 + half * 4) = v;
+                    }
+                    const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32;  // uniform; this lane: + c4 * 4
+                    const bool kok = ofm0 + c4 * 4 < a.Kb * 16;            // K not a multiple of the tile: padded channels are dropped
+                    const int soff = (ofm0 >> 4) * plane;
+                    floatx4 bias = {0.f, 0.f, 0.f, 0.f};
+                    if (FUSED && (epi & 1) && kok) bias = *reinterpret_cast<const floatx4 *>(a.bias + ofm0 + c4 * 4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        floatx4 v = *reinterpret_cast<const floatx4 *>(stage + (rp + 8 * i) * EPITCH + c4 * 4);
+                        const unsigned voff = kok ? vpix[i] : kOobOffset;
+                        if constexpr (FUSED) {
+                            // bias, max(., 0), optional rounding to bf16
+                            v += bias;
+                            if (epi & 2) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.f);
+                            }
+                        }
+                        // A vector-ALU write to the data registers of a multi-dword store issued just before it can
+                        // overtake the store's read of them on this hardware (the compiler only guards the form without
+                        // a scalar offset).  The empty asm keeps the stored registers live across a short s_nop, so
+                        // nothing can be scheduled or allocated into that window.
+                        if (bf16_out) {
+                            const uintx2_t h = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                            __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff, soff, kStoreWholeLines);
+                            asm volatile("s_nop 1" ::"v"(h[0]), "v"(h[1]));
+                        } else {
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, kStoreWholeLines);
+                            asm volatile("s_nop 1" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));
+                        }
                     }
                 }
             }
-            return;
-        }
-        // Fused epilogue: bias, max(., 0), optional rounding to bf16.  The values pass through temporaries that the
-        // next quad's arithmetic reuses; a vector-ALU write to the data registers of a multi-dword store issued just
-        // before it can overtake the store's read of them on this hardware (the compiler only guards the form
-        // without a scalar offset).  The empty asm keeps the stored registers live across a short s_nop, so nothing
-        // can be scheduled or allocated into that window.
-        const bool bf16_out = epi & 4;
-        const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, bf16_out ? a.out_bytes / 2 : a.out_bytes);
-        const int esz = bf16_out ? 2 : 4;
-        const int kb_stride = a.PQ * 16 * esz;
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int m = m0 + (wm * TM + tm) * 32 + l32;
-            int n, pq;
-            fast_divmod(m, a.PQ, a.magic_pq, n, pq);
-            const unsigned voff = m < a.M ? (unsigned)(((n * a.Kb * a.PQ + pq) * 16 + half * 4) * esz) : kOobOffset;
-#pragma unroll
-            for (int tk = 0; tk < TK; ++tk) {
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32 + rq * 8;
-                    if (ofm0 >= a.Kb * 16) continue;
-                    floatx4 v = {acc[tk][tm][rq * 4 + 0], acc[tk][tm][rq * 4 + 1], acc[tk][tm][rq * 4 + 2],
-                                 acc[tk][tm][rq * 4 + 3]};
-                    const int soff = (ofm0 >> 4) * kb_stride + (ofm0 & 15) * esz;
-                    if (epi & 1) v += *reinterpret_cast<const floatx4 *>(a.bias + ofm0 + half * 4);
-                    if (epi & 2) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
-                    }
-                    if (bf16_out) {
-                        const uintx2_t h = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                        __builtin_amdgcn_raw_buffer_store_b64(h, rout, voff, soff, 0);
-                        asm volatile("s_nop 1" ::"v"(h[0]), "v"(h[1]));
-                    } else {
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), rout, voff, soff, 0);
-                        asm volatile("s_nop 1" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));
-                    }
-                }
-            }
-        }
+        };
+        if (epi == 0)
+            store_tiles(std::false_type{});
+        else
+            store_tiles(std::true_type{});
         return;
     }
     // Split reduction without a workspace: partial tiles are added into the cleared output with fp32 atomics.  Issued from
@@ -237,8 +254,6 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
     // therefore turns its 32x32 tile around in a private LDS patch so that 16 consecutive lanes cover
     // one pixel's 16-channel line and an instruction adds into 4 whole lines.
     wait_vm_and_barrier<0>();  // zero-fill loads of the padded iterations may still be landing in the ring
-    float *stage = reinterpret_cast<float *>(lds) + wave * (32 * EPITCH);
-    const int rp = lane >> 3, c4 = lane & 7;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
