@@ -34,8 +34,8 @@ def kernel_source_digest(dtype: str) -> str:
     """Digest of the kernel sources of `dtype`: the stored HBM-traffic counters only describe the kernel they were
     taken on."""
     h = hashlib.sha256()
-    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip"] + (["conv_fwd_bf16_halo.h"] if dtype == "bf16" else
-                                                            ["conv_fwd_f32_n16.h", "conv_fwd_f32_n16_kloop.h"])
+    files = ["conv_fwd_kernel.h", f"conv_fwd_{dtype}.hip"] + (["conv_fwd_bf16_halo.h", "conv_fwd_bf16_shape.h", "conv_fwd_bf16_packed.hip"] if dtype == "bf16" else
+                                                            ["conv_fwd_f32_n16.h", "conv_fwd_f32_n16_kloop.h", "conv_fwd_f32_packed.hip"])
     for f in files:
         with open(os.path.join(ROOT, "paper_2002_02145_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
@@ -142,8 +142,8 @@ def _time_each(fn, launches: int):
 # scaled by a reference copy; see profiles/), keyed by a digest of the kernel sources they were taken with.
 # A different digest, a different tile picked by the model or a different inner loop means the launch is not the one the counters were
 # taken on: traffic is then reported as null.
-MEASURED_TRAFFIC = {"f32": ("62f2587ec80ca37b", (64, 176, 2, 1, 0), 3, 46594029),
-                    "bf16": ("061a84b313caf103", (64, 256, 2, 1, 0), 9, 34631505)}
+MEASURED_TRAFFIC = {"f32": ("8c2d4b94e5af9572", (64, 176, 2, 1, 0), 3, 46600889),
+                    "bf16": ("d9ac641d99c19d5d", (64, 256, 2, 1, 0), 9, 34630447)}
 
 
 def _layer_rows(ps, wl, torch, dtype_name: str, workspace, ws_cap: int):

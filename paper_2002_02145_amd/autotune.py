@@ -32,38 +32,55 @@ def _buffers(desc: ps.ConvDesc, es: int, copies: int = 1):
     return sets
 
 
+_SIDE = None   # the stream launches are captured on (one per process)
+
+
 def time_tile(desc: ps.ConvDesc, tile: ps.Tile | None, sets, warmup: int = 5, min_ms: float = 20.0,
-              max_iters: int = 2000, workspace=None) -> float:
+              max_iters: int = 2000, workspace=None, per_graph: int = 20) -> float:
     """Mean microseconds per launch of one tile (None = the library's own pick).  With a workspace tensor
-    the call goes through ps_conv2d_fwd_ws (split reductions use partial planes instead of atomics)."""
-    stream = torch.cuda.current_stream()
+    the call goes through ps_conv2d_fwd_ws (split reductions use partial planes instead of atomics).
+    The launches are captured into a HIP graph (`per_graph` of them, rotating through `sets`) and the graph is
+    replayed: many layers take 4-12 us per launch, about what one call through the Python binding costs the host, so a
+    loop of eager calls would time the interpreter.  Between dependent kernels of a graph lies the same gap as between
+    eager launches whose queue is full."""
+    global _SIDE
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
 
-    def launch(i):
+    def launch(i):   # on the current stream (the capturing one during capture)
         xb, wb, ob = sets[i % len(sets)]
         if workspace is not None:
-            ps.ps_conv2d_fwd_ws(desc, tile, xb, wb, ob, workspace, ws_bytes, stream)
+            ps.ps_conv2d_fwd_ws(desc, tile, xb, wb, ob, workspace, ws_bytes)
         elif tile is None:
-            ps.ps_conv2d_fwd(desc, xb, wb, ob, stream)
+            ps.ps_conv2d_fwd(desc, xb, wb, ob)
         else:
-            ps.ps_conv2d_fwd_tile(desc, tile, xb, wb, ob, stream)
+            ps.ps_conv2d_fwd_tile(desc, tile, xb, wb, ob)
 
     for i in range(warmup):
         launch(i)
     torch.cuda.synchronize()
+    per_graph = -(-per_graph // len(sets)) * len(sets)
+    if _SIDE is None:
+        _SIDE = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(_SIDE):
+        with torch.cuda.graph(graph, stream=_SIDE):
+            for i in range(per_graph):
+                launch(i)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
     # size the repetition count from a first timed batch
-    iters = 5
+    reps = 1
     while True:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        for i in range(iters):
-            launch(i)
+        for _ in range(reps):
+            graph.replay()
         e1.record(stream)
         e1.synchronize()
         ms = e0.elapsed_time(e1)
-        if ms >= min_ms or iters >= max_iters:
-            return ms * 1e3 / iters
-        iters = min(max_iters, max(iters * 2, int(iters * min_ms / max(ms, 1e-3)) + 1))
+        if ms >= min_ms or reps * per_graph >= max_iters:
+            return ms * 1e3 / (reps * per_graph)
+        reps = min(-(-max_iters // per_graph), max(reps * 2, int(reps * min_ms / max(ms, 1e-3)) + 1))
 
 
 def sweep(shape: wl.ConvShape, dtype: int = ps.PS_F32, min_ms: float = 20.0, cold: bool = False,

@@ -56,7 +56,7 @@ struct Chip {
     double l2_hit_latency_clk = 700.0;        // ... when the layer stays resident in L2 between launches
     double fill_clk = 4500.0;                 // first loads of a workgroup (nothing to overlap with)
     double launch_us = 1.5;
-    double dependent_launch_us = 5.0;         // a kernel that has to wait for the previous one to drain
+    double dependent_launch_us = 3.5;         // a kernel that has to wait for the previous one to drain (measured gap)
     double plane_latency_us = 0.3;            // per partial plane: the adding pass reads them one after another
     double reduce_ineff = 2.0;                // the plane-adding pass against streaming bandwidth
 };
