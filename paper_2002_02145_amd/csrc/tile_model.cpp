@@ -55,6 +55,7 @@ struct Chip {
     double load_latency_clk = 1150.0;         // global load to LDS under load, served from beyond one XCD's L2
     double l2_hit_latency_clk = 700.0;        // ... when the layer stays resident in L2 between launches
     double fill_clk = 4500.0;                 // first loads of a workgroup (nothing to overlap with)
+    double fill_clk_16 = 6750.0;              // ... per round of resident workgroups in the 16-bit kernels (with the epilogue's barrier and pass through LDS)
     double launch_us = 1.5;
     double dependent_launch_us = 3.5;         // a kernel that has to wait for the previous one to drain (measured gap)
     double plane_latency_us = 0.3;            // per partial plane: the adding pass reads them one after another
@@ -239,7 +240,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         // shows is the fill of every round of resident workgroups
         const double rounds = std::ceil(per_cu / occ);
         const double clk_epi = tiles_wave * (t.c_split > 1 && !with_ws ? 900.0 : 250.0);
-        t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk +
+        t_mfma = (per_simd * (clk_wave + clk_iter_overhead + clk_epi) + rounds * c.fill_clk_16 +
                   per_cu * (t.ring - 2) * 250.0) / c.clock_hz;
     }
 

@@ -37,9 +37,8 @@ def _losses(fname, dtype):
     ("sweep_bf16_N28.jsonl", ps.PS_BF16, 0.12, 0.03),     # 1x1 256->1024 at 14x14: 8.6 against 8.0 us (11.8 %)
     ("sweep_f32_N8.jsonl", ps.PS_F32, 0.10, 0.04),
     ("sweep_f32_N1.jsonl", ps.PS_F32, 0.13, 0.03),
-    # 16-bit layers at small batch take 3-12 us, mostly fixed costs that the model prices coarsely: the 7x7 stem at
-    # N = 8 is the worst case (a 256-pixel tile that fits the chip in one round runs 11.3 us, the pick 14.8 us)
-    ("sweep_bf16_N8.jsonl", ps.PS_BF16, 0.32, 0.09),
+    # 16-bit layers at small batch take 3-12 us, mostly fixed costs that the model prices coarsely
+    ("sweep_bf16_N8.jsonl", ps.PS_BF16, 0.17, 0.07),
     ("sweep_bf16_N1.jsonl", ps.PS_BF16, 0.20, 0.07),
 ])
 def test_pick_is_close_to_the_sweeps_best(fname, dtype, worst, mean):
