@@ -135,6 +135,21 @@ def test_specialised_shapes_are_refused_where_they_do_not_apply(ps):
     d = ps.ConvDesc.of(S(2, 64, 8, 8, 256, 1, 1, 1, 0))
     assert ps.KERNEL_NAMES[ps.ps_tile_kernel(d, ps.Tile(*stationary))] == "1x1 pixel-stationary"
     assert ps.KERNEL_NAMES[ps.ps_tile_kernel(ps.ConvDesc.of(S(2, 3, 20, 20, 64, 7, 7, 2, 3)), ps.Tile(*n16))] == "tap-packed"
+    # the tap-packed loops of the other first-layer filter sizes: 3x3, 5x5, 11x11 over at most 3 channels in fp32
+    # (16x16- and 32x32-tile kernels), over at most 8 in 16 bits; never for a split range
+    kernel = lambda shape, tile, dtype=ps.PS_F32: ps.KERNEL_NAMES[ps.ps_tile_kernel(ps.ConvDesc.of(shape, dtype), ps.Tile(*tile))]
+    for F, stride, pad in ((3, 2, 1), (5, 1, 2), (11, 4, 0)):
+        first = S(2, 3, 40, 40, 64, F, F, stride, pad)
+        assert kernel(first, n16) == "tap-packed" and kernel(first, (64, 128, 2, 1, 0)) == "tap-packed"
+        assert kernel(first, (64, 128, 2, 1, 0), ps.PS_BF16) == "tap-packed"
+        assert kernel(S(2, 8, 40, 40, 64, F, F, stride, pad), (64, 128, 2, 1, 0), ps.PS_BF16) == "tap-packed"
+        assert kernel(S(2, 9, 40, 40, 64, F, F, stride, pad), (64, 128, 2, 1, 0), ps.PS_BF16) != "tap-packed"
+        four = S(2, 4, 40, 40, 64, F, F, stride, pad)
+        assert kernel(four, (64, 128, 2, 1, 0)) != "tap-packed"       # fp32 packs four channels for 7x7 only
+        assert valid(four, n16) == (F == 3) and (F != 3 or kernel(four, n16) == "3x3 baked")
+    assert kernel(S(2, 3, 40, 40, 64, 3, 3, 1, 1), (64, 128, 2, 3, 0)) == "general"        # split range: not packed
+    assert kernel(S(2, 3, 40, 40, 64, 9, 9, 1, 4), (64, 128, 2, 1, 0)) == "general"        # no packed loop for 9x9
+    assert kernel(S(2, 3, 12, 12, 64, 3, 3, 1, 1), (64, 128, 2, 1, 0), ps.PS_BF16) == "3x3 patch"   # the patch loop keeps its layers
 
 
 def test_tile_cache_matches_uncached_selection_under_threads(ps):
