@@ -133,6 +133,22 @@ def first_layers(N: int = MINIBATCH) -> list[ConvShape]:
     ]
 
 
+def random_first_layer_shapes(count: int, seed: int) -> list[ConvShape]:
+    """Seeded small shapes of the first-layer kind: 1 to 8 input channels (three most often), square filters of side 3, 5, 7 or 11,
+    strides 1-4, pads from none to more than the filter needs, images just large enough up to 40 pixels."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        F = int(rng.choice([3, 5, 7, 11]))
+        stride, pad = int(rng.integers(1, 5)), int(rng.integers(0, F // 2 + 2))
+        H, W = int(rng.integers(1, 41)), int(rng.integers(1, 41))
+        if H + 2 * pad < F or W + 2 * pad < F:
+            continue
+        out.append(ConvShape(int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 3, 3, 4, 6, 8])), H, W, 16 * int(rng.integers(1, 9)), F, F,
+                             stride, pad, f"first{len(out)}_seed{seed}"))
+    return out
+
+
 def sweep_seed(layer_index: int) -> int:
     return 100 + layer_index
 

@@ -33,3 +33,19 @@ def test_random_shape_is_exact_on_integers_and_within_tolerance_on_reals(shape):
         out, mag = oracle.conv2d_fwd(shape, x, w)
         err = oracle.normalised_error(run_conv(shape, x, w, dtype), out, mag)
         assert err <= TOL[dtype], f"{shape} dtype={dtype}: err {err}"
+
+
+@pytest.mark.parametrize("shape", wl.random_first_layer_shapes(16, seed=77), ids=lambda s: s.name)
+def test_random_first_layer_shape_every_tile_is_exact_on_integers(shape):
+    """Few input channels and square filters of side 3, 5, 7, 11: the layers the tap-packed loops take (where channel
+    count and element type allow; the others run the ordinary loops).  Every candidate tile, both element types,
+    integer inputs, equality with the oracle."""
+    from gpu_util import run_conv, all_tiles
+    xi, wi = wl.small_integers(shape, 13)
+    exact, _ = oracle.conv2d_fwd(shape, xi, wi)
+    for dtype in (0, 1):
+        tiles = all_tiles(shape, dtype)
+        assert tiles, f"no candidate tile for {shape}"
+        for t in [None] + tiles:
+            got = run_conv(shape, xi, wi, dtype, t, ws=t is not None and t.c_split > 1)
+            assert np.array_equal(got.astype(np.float64), exact), f"{shape} dtype={dtype} tile={t and t.as_tuple()}"
