@@ -199,7 +199,7 @@ int ps_tile_autotune(const ps_conv_desc *d, int k, const void *in_blk, const voi
                      size_t workspace_bytes, void *stream, ps_tile *best, double *best_us);
 
 /* Which inner loop the library runs for tile `t` on `d` (for reports and tests): the loop with a runtime filter size,
- * the loops with a 1x1 or 3x3 filter baked in, the loops for 3x3, 5x5, 7x7 and 11x11 filters over at most 3 (fp32; 7x7:
+ * the loops with a 1x1, 3x3 or 5x5 filter baked in, the loops for 3x3, 5x5, 7x7 and 11x11 filters over at most 3 (fp32; 7x7:
  * 4) or 8 (16-bit) input channels that pack four (two) taps into one batch element, the 16-bit 3x3 loop that stages the input patch once per c-block, or the fp32 1x1 loop that keeps a
  * tile's pixels with all 64 input channels in LDS and walks over four 64-channel output tiles (tile kt = 256).
  * Negative ps_status if the tile is not valid for the descriptor. */
@@ -208,6 +208,7 @@ typedef enum {
     PS_KERNEL_1X1 = 1,
     PS_KERNEL_STATIONARY_1X1 = 2,
     PS_KERNEL_3X3 = 3,
+    PS_KERNEL_5X5 = 5,
     PS_KERNEL_PACKED_TAPS = 7,
     PS_KERNEL_PATCH_3X3 = 9
 } ps_kernel_variant;

@@ -244,7 +244,7 @@ def ps_conv2d_fwd_fused(desc: ConvDesc, tile, in_blk, wt_blk, out_blk, workspace
                                    _ptr(workspace) or None, int(workspace_bytes), _stream(stream)), "ps_conv2d_fwd_fused")
 
 
-KERNEL_NAMES = {0: "general", 1: "1x1 baked", 2: "1x1 pixel-stationary", 3: "3x3 baked", 7: "tap-packed", 9: "3x3 patch"}
+KERNEL_NAMES = {0: "general", 1: "1x1 baked", 2: "1x1 pixel-stationary", 3: "3x3 baked", 5: "5x5 baked", 7: "tap-packed", 9: "3x3 patch"}
 
 
 def ps_tile_kernel(desc: ConvDesc, tile: Tile) -> int:

@@ -81,7 +81,7 @@ bool kt_admissible(int K, int kt)
 }
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary, lds_3x3, lds_halo;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary, lds_3x3, lds_halo, has_5x5, lds_5x5;
 };
 
 int list_shapes(int dtype, ShapeInfo *out, int cap)
@@ -91,7 +91,7 @@ int list_shapes(int dtype, ShapeInfo *out, int cap)
     n = n < cap ? n : cap;
     for (int i = 0; i < n; ++i) out[i] = ShapeInfo{tab[i].kt, tab[i].mt, tab[i].ring, tab[i].threads, tab[i].lds_bytes, tab[i].group,
                                                    tab[i].launch_halo ? tab[i].halo_bytes : 0, tab[i].launch == nullptr, tab[i].stationary,
-                                                   tab[i].lds_3x3, tab[i].lds_halo};
+                                                   tab[i].lds_3x3, tab[i].lds_halo, tab[i].launch_5x5 != nullptr, tab[i].lds_5x5};
     return n;
 }
 
@@ -102,7 +102,7 @@ int tile_valid(const Dims &dm, const ps_tile &t)
     const ShapeEntry *sh = find_shape(dm.dtype, t.kt, t.mt, t.ring);
     if (!sh) return PS_EUNSUPPORTED;
     // shapes without a loop for a runtime filter size and without an atomic epilogue: 1x1 and 3x3, unsplit
-    if (!sh->launch && !(t.c_split == 1 && ((dm.R == dm.S && (dm.R == 1 || dm.R == 3)) ||
+    if (!sh->launch && !(t.c_split == 1 && ((dm.R == dm.S && (dm.R == 1 || dm.R == 3 || dm.R == 5)) ||
                                             (packs_taps(dm) && dm.C <= 3 && sh->launch_packed))))
         return PS_EUNSUPPORTED;
     // pixel-stationary shapes: 1x1 filters over exactly 4 c-blocks, images of at least 16 pixels
@@ -143,6 +143,7 @@ int kernel_variant(const Dims &dm, const ps_tile &t, const ShapeEntry &sh)
     if (dm.R == dm.S && nb_split % (dm.R * dm.S) == 0) {
         if (dm.R == 1 && sh.launch_1x1) return PS_KERNEL_1X1;
         if (dm.R == 3 && sh.launch_3x3) return PS_KERNEL_3X3;
+        if (dm.R == 5 && sh.launch_5x5) return PS_KERNEL_5X5;
     }
     return PS_KERNEL_GENERAL;
 }
@@ -197,6 +198,7 @@ int build_plan(const Dims &dm, const ps_tile &t, Plan *pl)
     case PS_KERNEL_1X1:
     case PS_KERNEL_STATIONARY_1X1: pl->fn = sh->launch_1x1; break;
     case PS_KERNEL_3X3: pl->fn = sh->launch_3x3; break;
+    case PS_KERNEL_5X5: pl->fn = sh->launch_5x5; break;
     case PS_KERNEL_PATCH_3X3: pl->fn = sh->launch_halo; break;
     case PS_KERNEL_PACKED_TAPS:
         pl->fn = sh->launch_packed;

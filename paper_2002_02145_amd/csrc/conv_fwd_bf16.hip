@@ -221,6 +221,8 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_kernel(const ConvA
         for (int s0 = 0; s0 < nslot; s0 += U, cb0 += U * G / TAPS) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                // a range of whole c-blocks that does not fill the unrolled block ends at a c-block boundary
+                if (TAPS > 1 && TAPS % G == 0 && u > 0 && u % TG == 0 && s0 + u >= nslot) break;
                 wait_vm_and_barrier<(D - 2) * LPS>();
                 read_frags((u + 1) % NBUF, (u + 1) % 2);
                 issue_baked_bf16<Sh, NBUF, G, NTAP, APW, WPW>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,
@@ -265,14 +267,22 @@ void launch_bf16(const ConvArgs &a, unsigned grid, hipStream_t st)
     hipLaunchKernelGGL((conv_fwd_bf16_kernel<KT, MT, WK, WM, NBUF, G, SIDE>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
 }
 
-// G batch elements per iteration; the 3x3-baked kernels take one filter row (3 elements) per iteration
+template <int KT, int MT, int WK, int WM, int NBUF>
+void launch_bf16_5x5(const ConvArgs &a, unsigned grid, hipStream_t st)
+{
+    if constexpr (bf16_5x5_fits<KT, MT, WK, WM, NBUF>())
+        hipLaunchKernelGGL((conv_fwd_bf16_kernel<KT, MT, WK, WM, NBUF, 5, 5>), dim3(grid), dim3(64 * WK * WM), 0, st, a);
+}
+
+// G batch elements per iteration; the 3x3- and 5x5-baked kernels take one filter row (3 or 5 elements) per iteration
 #define PS_BF16_SHAPE(KT, MT, WK, WM, NBUF, G)                                                          \
     {PS_BF16, KT, MT, NBUF, 64 * WK * WM, Bf16Shape<KT, MT, WK, WM, NBUF, G>::LDS_BYTES, G,              \
      &launch_bf16<KT, MT, WK, WM, NBUF, G, 0>, &launch_bf16<KT, MT, WK, WM, NBUF, G, 1>,                 \
      &launch_bf16<KT, MT, WK, WM, NBUF, 3, 3>, &launch_bf16_packed<KT, MT, WK, WM, NBUF, G>,           \
      halo_launch_or_null<KT, MT, WK, WM, NBUF>(),                                                        \
      halo_capacity_bytes<MT>(), 0, Bf16Shape<KT, MT, WK, WM, NBUF, 3>::LDS_BYTES,                        \
-     halo_lds_bytes_or_zero<KT, MT, WK, WM, NBUF>()}
+     halo_lds_bytes_or_zero<KT, MT, WK, WM, NBUF>(),                                                     \
+     bf16_5x5_or_null<KT, MT, WK, WM, NBUF>(), bf16_5x5_lds_or_zero<KT, MT, WK, WM, NBUF>()}
 #define PS_TABLE_ROW(KT, MT, WK, WM, G) PS_BF16_SHAPE(KT, MT, WK, WM, 2, G), PS_BF16_SHAPE(KT, MT, WK, WM, 4, G),
 static const ShapeEntry kBf16Shapes[] = {PS_BF16_SHAPE_LIST(PS_TABLE_ROW)};
 

@@ -185,6 +185,7 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_bf16_halo_kernel(const 
     for (int c0 = 0; c0 < ncb; c0 += 2) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
+            if (c > 0 && c0 + c >= ncb) break;  // an odd number of c-blocks ends here
 #pragma unroll
             for (int t = 0; t < 9; ++t) {
                 const int par = (c * 9 + t) % 2;

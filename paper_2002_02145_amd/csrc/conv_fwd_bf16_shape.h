@@ -35,6 +35,33 @@ struct Bf16Shape {
 // conv_fwd_bf16_packed.hip)
 template <int KT, int MT, int WK, int WM, int NBUF, int G>
 void launch_bf16_packed(const ConvArgs &a, unsigned grid, hipStream_t st);
+// the loop with a 5x5 filter baked in, one filter row (5 batch elements) per iteration (conv_fwd_bf16.hip); not
+// compiled where that ring does not fit LDS or the wait counter's range
+template <int KT, int MT, int WK, int WM, int NBUF>
+void launch_bf16_5x5(const ConvArgs &a, unsigned grid, hipStream_t st);
+template <int KT, int MT, int WK, int WM, int NBUF>
+constexpr bool bf16_5x5_fits()
+{
+    constexpr int NW = WK * WM, LPS = 5 * ((MT / 32 + NW - 1) / NW + (KT / 32 + NW - 1) / NW);
+    // (eight-wave shapes have 256 registers per lane: five elements' fragments next to 64 accumulators do not fit)
+    return NW <= 4 && NBUF * 5 * (MT + KT) * 32 + 1024 <= 160 * 1024 && (NBUF - 2) * LPS <= 63;
+}
+template <int KT, int MT, int WK, int WM, int NBUF>
+constexpr LaunchFn bf16_5x5_or_null()
+{
+    if constexpr (bf16_5x5_fits<KT, MT, WK, WM, NBUF>())
+        return &launch_bf16_5x5<KT, MT, WK, WM, NBUF>;
+    else
+        return nullptr;
+}
+template <int KT, int MT, int WK, int WM, int NBUF>
+constexpr int bf16_5x5_lds_or_zero()
+{
+    if constexpr (bf16_5x5_fits<KT, MT, WK, WM, NBUF>())
+        return Bf16Shape<KT, MT, WK, WM, NBUF, 5>::LDS_BYTES;
+    else
+        return 0;
+}
 
 // Every shape is compiled with rings of 2 and 4 slots.
 //                      KT   MT  WK WM  G        wave tile (channels x pixels)

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     // SIDE = 33, 35, 37, 311: F x F filter over at most 3 input channels, tap-packed as in conv_fwd_kernel.h (a batch
     // element holds 4 consecutive taps x [c0 c1 c2 0]); chunk g of a pixel is then tap g and MFMA step t is channel t,
     // so step 3 would only multiply the padding lane and is left out.
-    static_assert(SIDE == 1 || SIDE == 3 || (side_packs(SIDE) && side_skips_c3(SIDE)), "filter sizes with a baked loop");
+    static_assert(SIDE == 1 || SIDE == 3 || SIDE == 5 || (side_packs(SIDE) && side_skips_c3(SIDE)), "filter sizes with a baked loop");
     constexpr bool PACKED = side_packs(SIDE);
     constexpr int FS = side_filter(SIDE);
     constexpr int TAPS = PACKED ? (FS * FS + 3) / 4 : SIDE * SIDE;
@@ -158,6 +158,8 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (PACKED && u >= TAPS) break;  // a tap-packed range is exactly TAPS elements (an odd number)
+            // a range of whole c-blocks that does not fill the unrolled block ends at a c-block boundary
+            if (baked_loop_exits(TAPS, NBUF) && !PACKED && u > 0 && u % TAPS == 0 && b0 + u >= nb) break;
             wait_vm_and_barrier<(D - 2) * LPE>();
             PS_N16_READ((u + 1) % NBUF, (u + 1) % 2)
             issue_baked_fn<Sh, NBUF, TAPS, APW, WPW, PACKED>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF,
@@ -287,12 +289,15 @@ void launch_f32_n16(const ConvArgs &a, unsigned grid, hipStream_t st)
 // conv_fwd_f32_packed.hip)
 template <int MT, int NBUF>
 void launch_f32_n16_packed(const ConvArgs &a, unsigned grid, hipStream_t st);
+template <int MT, int NBUF>
+void launch_f32_n16_5x5(const ConvArgs &a, unsigned grid, hipStream_t st);
 
-// No loop with a runtime filter size and no atomic epilogue: the enumerator offers these shapes for 1x1 and 3x3
+// No loop with a runtime filter size and no atomic epilogue: the enumerator offers these shapes for 1x1, 3x3 and 5x5
 // filters and for the tap-packed filters over at most 3 channels, unsplit.
 #define PS_F32_N16_SHAPE(MT, NBUF)                                                                  \
     {PS_F32, 64, MT, NBUF, 256, N16Shape<MT, NBUF>::LDS_BYTES, 1, nullptr, &launch_f32_n16<MT, NBUF, 1>, \
-     &launch_f32_n16<MT, NBUF, 3>, &launch_f32_n16_packed<MT, NBUF>, nullptr, 0}
+     &launch_f32_n16<MT, NBUF, 3>, &launch_f32_n16_packed<MT, NBUF>, nullptr, 0, 0, 0, 0,             \
+     &launch_f32_n16_5x5<MT, NBUF>, 0}
 #define PS_F32_N16_SHAPE_LIST(X) X(48, 2) X(48, 4) X(96, 2) X(96, 4) X(176, 2) X(176, 4)
 
 }  // namespace ps

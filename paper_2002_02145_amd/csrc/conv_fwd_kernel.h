@@ -347,9 +347,12 @@ __device__ __forceinline__ void issue_baked_fn(const ConvArgs &a, char *lds, con
 }
 
 constexpr int ct_gcd(int x, int y) { return y == 0 ? x : ct_gcd(y, x % y); }
+// Whether the unrolled block of a baked loop (lcm(ring, taps) batch elements) can be left at a c-block boundary: the
+// compiler unrolls a loop with such an exit only up to a certain length (the host's padded_elems mirrors this).
+constexpr bool baked_loop_exits(int taps, int ring) { return taps > 1 && ring / ct_gcd(ring, taps) * taps <= 50; }
 
 // Codes of the loops with the filter baked in (template argument SIDE of the fp32 kernels):
-//   1, 3        R = S = SIDE, 16 channels of one tap per batch element;
+//   1, 3, 5     R = S = SIDE, 16 channels of one tap per batch element;
 //   7           tap-packed 7x7 over at most 4 input channels (4 taps x 4 channels per batch element);
 //   30 + F      tap-packed F x F over at most 3 input channels, F = 3, 5, 7 (the zero fourth lane is never multiplied);
 //   311         the same for 11 x 11.
@@ -572,6 +575,9 @@ __global__ __launch_bounds__(64 * WK * WM) void conv_fwd_f32_kernel(const ConvAr
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (PACK4 && u >= TAPS) break;  // a tap-packed range is exactly TAPS elements (an odd number)
+                // a range of whole c-blocks that does not fill the unrolled block ends at a c-block boundary (one
+                // scalar compare per c-block; 1x1 ranges, and blocks too long to unroll with an exit, stay padded)
+                if (baked_loop_exits(TAPS, NBUF) && !PACK4 && u > 0 && u % TAPS == 0 && b0 + u >= nb) break;
                 wait_vm_and_barrier<(D - 2) * LPE>();
                 read_frags((u + 1) % NBUF, (u + 1) % 2);
                 issue_baked_fn<Sh, NBUF, NTAP, APW, WPW, PACK4, SIDE>(a, lds, vtap, wsoff, wok, vw, wave, u % NBUF, u + NBUF,
@@ -628,6 +634,8 @@ struct ShapeEntry {
     int stationary;       // 1: pixels with all their input channels stay in LDS (1x1 filters, C = 64 only)
     int lds_3x3;          // LDS bytes of launch_3x3 / launch_halo where they differ from lds_bytes (0 = the same):
     int lds_halo;         // the tile model prices occupancy with the footprint of the loop that will run
+    LaunchFn launch_5x5;  // R = S = 5 baked in (nullptr if not compiled)
+    int lds_5x5;          // LDS bytes of launch_5x5 where they differ from lds_bytes (0 = the same)
 };
 
 template <int KT, int MT, int WK, int WM, int NBUF, int SIDE>
@@ -640,11 +648,15 @@ void launch_f32(const ConvArgs &a, unsigned grid, hipStream_t st)
 // instantiated in conv_fwd_f32_packed.hip)
 template <int KT, int MT, int WK, int WM, int NBUF>
 void launch_f32_packed(const ConvArgs &a, unsigned grid, hipStream_t st);
+// the loop with a 5x5 filter baked in (same translation unit)
+template <int KT, int MT, int WK, int WM, int NBUF>
+void launch_f32_5x5(const ConvArgs &a, unsigned grid, hipStream_t st);
 
 #define PS_F32_SHAPE(KT, MT, WK, WM, NBUF)                                                              \
     {PS_F32, KT, MT, NBUF, 64 * WK * WM, F32Shape<KT, MT, WK, WM, NBUF>::LDS_BYTES, 1,                   \
      &launch_f32<KT, MT, WK, WM, NBUF, 0>, &launch_f32<KT, MT, WK, WM, NBUF, 1>,                        \
-     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32_packed<KT, MT, WK, WM, NBUF>, nullptr, 0}
+     &launch_f32<KT, MT, WK, WM, NBUF, 3>, &launch_f32_packed<KT, MT, WK, WM, NBUF>, nullptr, 0, 0, 0, 0,    \
+     &launch_f32_5x5<KT, MT, WK, WM, NBUF>, 0}
 
 //               KT   MT  WK WM NBUF       wave tile (channels x pixels)
 // Ring depths: a load has (NBUF - 1) iterations to land, and an iteration lasts 512 matrix-core cycles

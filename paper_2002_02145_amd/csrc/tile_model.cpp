@@ -28,7 +28,7 @@
 namespace ps {
 
 struct ShapeInfo {
-    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary, lds_3x3, lds_halo;
+    int kt, mt, ring, threads, lds_bytes, group, halo_bytes, baked_only, stationary, lds_3x3, lds_halo, has_5x5, lds_5x5;
 };
 int list_shapes(int dtype, ShapeInfo *out, int cap);  // api.hip
 bool halo_applies(const Dims &dm, const ps_tile &t, int capacity_bytes);  // api.hip
@@ -64,12 +64,14 @@ struct Chip {
 
 const Chip kChip;
 
-// The kernels with a baked 1x1 or 3x3 filter issue no vector-ALU work in their loop; their loop is unrolled
-// over lcm(ring, R*S) batch elements and the range is padded to a multiple of that.
-bool baked_filter(const Dims &dm, int nb_split)
+// The kernels with a baked 1x1, 3x3 or 5x5 filter issue no vector-ALU work in their loop; their loop is unrolled
+// over lcm(ring, R*S) batch elements and the range is padded to a multiple of that.  (A 16-bit shape whose ring of
+// filter rows does not fit LDS has no 5x5 loop and runs the general one.)
+bool baked_filter(const Dims &dm, const ShapeInfo &sh, int nb_split)
 {
     if (packs_taps(dm)) return nb_split == dm.NB;  // unsplit only
-    return dm.R == dm.S && (dm.R == 1 || dm.R == 3) && nb_split % (dm.R * dm.S) == 0;
+    if (dm.R == 5 && !sh.has_5x5) return false;
+    return dm.R == dm.S && (dm.R == 1 || dm.R == 3 || dm.R == 5) && nb_split % (dm.R * dm.S) == 0;
 }
 
 // The pixel-stationary fp32 kernels: 1x1 filters over exactly 4 c-blocks (everything a pixel needs fits in LDS next
@@ -88,7 +90,7 @@ int group_of(const Dims &dm, const ShapeInfo &sh, int nb_split, bool patch = fal
 {
     if (dm.dtype == PS_F32) return 1;
     if (packed_runs(dm, nb_split, patch)) return sh.group;
-    return baked_filter(dm, nb_split) && dm.R == 3 ? 3 : sh.group;  // (the patch kernel: see model_cost)
+    return baked_filter(dm, sh, nb_split) && dm.R >= 3 ? dm.R : sh.group;  // one filter row (the patch kernel: see model_cost)
 }
 
 // batch elements the kernel really iterates over for a range of nb_split (c-block, r, s) triples
@@ -101,14 +103,16 @@ int padded_elems(const Dims &dm, const ShapeInfo &sh, int nb_split, bool patch =
         const int g = group_of(dm, sh, nb_split, patch);
         // tap-packed: two taps per element, g elements per iteration
         if (packed_runs(dm, nb_split, patch)) return ((dm.R * dm.S + 1) / 2 + g - 1) / g * g;
+        // baked 3x3 / 5x5 and the patch loop: whole filter rows per iteration, the loop leaves at a c-block boundary
+        if (g == 3 || g == 5) return nb_split;
         unit = ring * g;
-        if (g == 3) unit = ring % 3 == 0 ? ring * 3 : ring * 9;  // lcm(ring, 3) iterations of 3 elements
-    } else if (baked_filter(dm, nb_split)) {
+    } else if (baked_filter(dm, sh, nb_split)) {
         if (packs_taps(dm)) return (dm.R * dm.S + 3) / 4;  // four taps per element, in one pass of exactly that many iterations
         const int taps = dm.R * dm.S;
         int g = ring, h = taps;
         while (h) { const int r = g % h; g = h; h = r; }
-        unit = ring / g * taps;
+        unit = ring / g * taps;                             // lcm(ring, taps): the unrolled block
+        if (taps > 1 && unit <= 50) return nb_split;        // ... which the kernel leaves at a c-block boundary where it is short enough
     }
     return (nb_split + unit - 1) / unit * unit;
 }
@@ -140,7 +144,7 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     const bool patch = sh.halo_bytes > 0 && halo_applies(dm, t, sh.halo_bytes);
     const bool packed = packed_runs(dm, dm.NB / t.c_split, patch);
     const double nb_pad = padded_elems(dm, sh, dm.NB / t.c_split, patch);  // zero elements pad the range
-    const bool baked = baked_filter(dm, dm.NB / t.c_split);
+    const bool baked = baked_filter(dm, sh, dm.NB / t.c_split);
     const double es = dm.es;
     const double waves_wg = sh.threads / 64.0;
 
@@ -155,6 +159,8 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
         lds_used = sh.lds_halo;
     else if (dm.dtype != PS_F32 && baked && dm.R == 3 && !packed && sh.lds_3x3 > 0)
         lds_used = sh.lds_3x3;
+    else if (dm.dtype != PS_F32 && baked && dm.R == 5 && !packed && sh.lds_5x5 > 0)
+        lds_used = sh.lds_5x5;
     double occ = std::floor(c.lds_bytes / lds_used);
     occ = std::max(1.0, std::min(occ, std::floor(waves_simd * 4.0 / waves_wg)));
 
@@ -313,7 +319,7 @@ void enumerate(const Dims &dm, std::vector<Cand> &out)
         if (s.mt > 64 && s.mt >= 2 * dm.M) continue;
         const long long n_mt = (dm.M + s.mt - 1) / s.mt;
         const long long base_wg = n_mt * ((dm.K + s.kt - 1) / s.kt);
-        if (s.baked_only && !((dm.R == dm.S && (dm.R == 1 || dm.R == 3)) || (packs_taps(dm) && dm.C <= 3 && !s.stationary)))
+        if (s.baked_only && !((dm.R == dm.S && (dm.R == 1 || dm.R == 3 || dm.R == 5)) || (packs_taps(dm) && dm.C <= 3 && !s.stationary)))
             continue;
         if (s.stationary && !stationary_applies(dm)) continue;
         for (int sp : splits) {

@@ -29,4 +29,7 @@ EDGE_SHAPES = [
     ConvShape(1, 3, 27, 23, 96, 11, 11, 4, 0, "11x11s4_C3_K96_nopad"),
     ConvShape(1, 6, 10, 9, 32, 5, 5, 2, 2, "5x5_C6_K32"),               # packed in 16 bits only
     ConvShape(1, 4, 8, 8, 16, 3, 3, 1, 1, "3x3_C4_fp32_not_packed"),    # four channels: only 7x7 packs them in fp32
+    # loops with a 5x5 filter baked in
+    ConvShape(2, 32, 9, 11, 64, 5, 5, 1, 2, "5x5_C32_K64"),
+    ConvShape(1, 48, 13, 8, 96, 5, 5, 2, 1, "5x5s2_C48_K96"),           # three c-blocks: rings of 2 and 4 both pad the range
 ]

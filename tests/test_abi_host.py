@@ -126,7 +126,8 @@ def test_specialised_shapes_are_refused_where_they_do_not_apply(ps):
     assert not valid(S(2, 64, 8, 8, 256, 1, 1, 1, 0), (256, 176, 2, 2, 0))  # no split reduction
     assert not valid(S(2, 64, 8, 8, 256, 1, 1, 1, 0), stationary, ps.PS_BF16)
     assert valid(S(2, 64, 8, 8, 64, 3, 3, 1, 1), n16) and valid(S(2, 64, 8, 8, 64, 1, 1, 2, 0), n16)
-    assert not valid(S(2, 64, 8, 8, 64, 5, 5, 1, 2), n16)                   # no baked 5x5 loop
+    assert valid(S(2, 64, 8, 8, 64, 5, 5, 1, 2), n16)                       # 5x5 has a baked loop too
+    assert not valid(S(2, 64, 8, 8, 64, 4, 4, 1, 2), n16)                   # no baked 4x4 loop
     assert not valid(S(2, 64, 8, 8, 64, 3, 3, 1, 1), (64, 176, 2, 2, 0))    # no atomic epilogue
     assert valid(S(2, 3, 20, 20, 64, 7, 7, 2, 3), n16)                      # tap-packed stem, 3 channels
     assert not valid(S(2, 4, 20, 20, 64, 7, 7, 2, 3), n16)                  # 4 channels: only the 32x32 kernels
@@ -146,7 +147,7 @@ def test_specialised_shapes_are_refused_where_they_do_not_apply(ps):
         assert kernel(S(2, 9, 40, 40, 64, F, F, stride, pad), (64, 128, 2, 1, 0), ps.PS_BF16) != "tap-packed"
         four = S(2, 4, 40, 40, 64, F, F, stride, pad)
         assert kernel(four, (64, 128, 2, 1, 0)) != "tap-packed"       # fp32 packs four channels for 7x7 only
-        assert valid(four, n16) == (F == 3) and (F != 3 or kernel(four, n16) == "3x3 baked")
+        assert valid(four, n16) == (F in (3, 5)) and (F not in (3, 5) or kernel(four, n16) == f"{F}x{F} baked")
     assert kernel(S(2, 3, 40, 40, 64, 3, 3, 1, 1), (64, 128, 2, 3, 0)) == "general"        # split range: not packed
     assert kernel(S(2, 3, 40, 40, 64, 9, 9, 1, 4), (64, 128, 2, 1, 0)) == "general"        # no packed loop for 9x9
     assert kernel(S(2, 3, 12, 12, 64, 3, 3, 1, 1), (64, 128, 2, 1, 0), ps.PS_BF16) == "3x3 patch"   # the patch loop keeps its layers
