@@ -408,9 +408,25 @@ def main(argv=None) -> int:
                              "algorithmic_bytes": b_alg},
                 "tile": list(hb.tile.as_tuple()), "kernel": ps.KERNEL_NAMES[ps.ps_tile_kernel(hb.d, hb.tile)],
                 "checked_against_oracle": hb.check(oracle) if oracle is not None else None}
+        # the epilogue fused into the store (bias, max(., 0)) and, for 16-bit inputs, a 16-bit output that the next
+        # layer reads as its blocked input: same layers, same tiles, graph replay
+        bias = torch.zeros(wl.CFG2.K, dtype=torch.float32, device=dev)
+        ob16 = torch.empty(ps.ps_blocked_out_bytes(hb.d) // 4, dtype=torch.bfloat16, device=dev)
+        fused = {}
+        for name, H, out, odt in (("f32_bias_relu_us", hl, hl.ob, ps.PS_F32), ("bf16_bias_relu_us", hb, hb.ob, ps.PS_F32),
+                                  ("bf16_bias_relu_bf16_out_us", hb, ob16, ps.PS_BF16)):
+            if H.shape is not wl.CFG2:
+                continue
+            fn = (lambda H=H, out=out, odt=odt: ps.ps_conv2d_fwd_fused(H.d, None, H.xb, H.wb, out, workspace, WS_CAP,
+                                                                       bias=bias, relu=True, out_dtype=odt))
+            gtf = _GraphTimer(fn)
+            _precondition(gtf.replay, 40.0)
+            fused[name] = round(gtf.time_us(100.0), 2)
+            del gtf
+        bf16["fused_epilogue"] = fused
         if not a.no_layers:
             bf16["layers"], bf16["layers_aggregate"] = _layer_rows(ps, wl, torch, "bf16", workspace, WS_CAP)
-        del hb
+        del hb, ob16
 
     peak = PEAK_TFLOPS[a.dtype]
     alg_bytes = shape.algorithmic_bytes(es)

@@ -72,6 +72,12 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     const int m0 = tc.mtile * MT;
     const int kb0 = tc.ktile * (Sh::KT / 16);
     const int b_begin = tc.split * a.nb_split;
+    // the fused kernel's bias, asked for before everything else (it is older than every load the loop counts, so the
+    // wait counts below hold; asked for in the epilogue it would cost a load's latency there)
+    floatx4_n bias = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (FUSED) {
+        if ((a.epi & 1) && kb0 + wave < a.Kb) bias = *reinterpret_cast<const floatx4_n *>(a.bias + (kb0 + wave) * 16 + g * 4);
+    }
 
     // ---- loader: one instruction fills 16 pixels (lane -> pixel lane/4, 16-byte chunk lane%4), offsets per tap.
     // In two stages: the taps the first D batch elements need, their loads, then the other taps under the latency of
@@ -191,8 +197,6 @@ __global__ __launch_bounds__(256) void conv_fwd_f32_n16_kernel(const ConvArgs a)
     float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
     const __amdgpu_buffer_rsrc_t rout = make_rsrc(base, bf16_out ? a.out_bytes / 2 : a.out_bytes);
     const int esz = bf16_out ? 2 : 4;
-    floatx4_n bias = {0.f, 0.f, 0.f, 0.f};
-    if (epi & 1) bias = *reinterpret_cast<const floatx4_n *>(a.bias + kb * 16 + g * 4);
 
 // what the fused epilogue does to one accumulator quad before it is stored
 #define PS_N16_FUSED_STORE(V_, VOFF_, SOFF_)                                                               \

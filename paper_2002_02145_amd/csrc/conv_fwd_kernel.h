@@ -138,16 +138,16 @@ __device__ inline void wait_vm_and_barrier()
 
 typedef unsigned uintx2_t __attribute__((ext_vector_type(2)));
 
-// Two fp32 values rounded to bf16 (nearest, ties to even), packed low | high << 16.  A NaN keeps its sign and the
-// upper payload bits and gets the quiet bit (the rounding add would otherwise carry a NaN whose only set mantissa
-// bits are low ones into the exponent: infinity).
-__device__ inline unsigned bf16_bits_rne(float x)
+// Two fp32 values rounded to bf16 (nearest, ties to even), packed low | high << 16: the hardware's packed conversion
+// (v_cvt_pk_bf16_f32, one instruction; a NaN stays a quiet NaN).  Done with integer arithmetic it took seven
+// instructions per value, a microsecond on a launch that stores 64 values per lane.
+typedef float floatx2_cvt __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_cvt __attribute__((ext_vector_type(2)));
+__device__ inline unsigned pack_bf16(float lo, float hi)
 {
-    const unsigned a = __builtin_bit_cast(unsigned, x);
-    const unsigned r = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
-    return (a & 0x7FFFFFFFu) > 0x7F800000u ? (a >> 16) | 0x40u : r;
+    const floatx2_cvt v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_cvt));
 }
-__device__ inline unsigned pack_bf16(float lo, float hi) { return bf16_bits_rne(lo) | (bf16_bits_rne(hi) << 16); }
 
 // Cache policy (auxiliary operand of the buffer-store builtins; bit 4 = sc1) of output stores whose every instruction
 // covers whole 64-byte lines, as in the 16x16-tile kernels: the line is written through L2 at once instead of
@@ -183,7 +183,19 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
         // out-of-range offset, which drops their store.
         float *const base = a.c_split == 1 ? a.out : a.partial + (size_t)tc.split * (size_t)a.out_elems;
         const int epi = a.c_split == 1 ? a.epi : 0;  // a split's partial planes stay raw; the adding pass applies it
-        wait_vm_and_barrier<0>();  // every wave has read its last fragments: the ring may be overwritten
+        // The bias of this lane's channel quads, asked for once and before the wait below (TK loads, which that wait
+        // leaves in flight: vector-memory operations retire in order, and everything older has to have landed).
+        floatx4 bias_q[TK];
+#pragma unroll
+        for (int tk = 0; tk < TK; ++tk) {
+            const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + c4 * 4;
+            bias_q[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if ((epi & 1) && ofm < a.Kb * 16) bias_q[tk] = *reinterpret_cast<const floatx4 *>(a.bias + ofm);
+        }
+        if (epi & 1)
+            wait_vm_and_barrier<TK>();
+        else
+            wait_vm_and_barrier<0>();  // every wave has read its last fragments: the ring may be overwritten
         // Two instances of the loop: the plain one has no branch between the LDS reads and the stores of a tile, so
         // the four reads are issued together and the stores follow as the data return.
         auto store_tiles = [&](auto fused_tag) {
@@ -213,11 +225,15 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
                     const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32;  // uniform; this lane: + c4 * 4
                     const bool kok = ofm0 + c4 * 4 < a.Kb * 16;            // K not a multiple of the tile: padded channels are dropped
                     const int soff = (ofm0 >> 4) * plane;
-                    floatx4 bias = {0.f, 0.f, 0.f, 0.f};
-                    if (FUSED && (epi & 1) && kok) bias = *reinterpret_cast<const floatx4 *>(a.bias + ofm0 + c4 * 4);
+                    const floatx4 bias = bias_q[tk];
+                    // all four reads first, so that the branches of the fused epilogue do not sit between a read and
+                    // its store (the reads' latency is then paid once per tile, not once per store)
+                    floatx4 vq[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vq[i] = *reinterpret_cast<const floatx4 *>(stage + (rp + 8 * i) * EPITCH + c4 * 4);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        floatx4 v = *reinterpret_cast<const floatx4 *>(stage + (rp + 8 * i) * EPITCH + c4 * 4);
+                        floatx4 v = vq[i];
                         const unsigned voff = kok ? vpix[i] : kOobOffset;
                         if constexpr (FUSED) {
                             // bias, max(., 0), optional rounding to bf16
