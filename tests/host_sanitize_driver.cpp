@@ -337,7 +337,7 @@ int main()
             reinterpret_cast<int32_t *>(&d)[field] = v;
             int32_t P, Q;
             if ((field == 8 && v == 0) || (field == 9 && v == 0)) continue;  // pad 0, dtype 0 are fine
-            // whatever the verdict, no call may misbehave; a verdict of "valid" must come with positive sizes
+            // whatever the answer, no call may misbehave; an answer of "valid" must come with positive sizes
             const bool valid = ps_out_dims(&d, &P, &Q) == PS_OK;
             drive_descriptor(d, valid, false);
         }
