@@ -187,15 +187,17 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
         // leaves in flight: vector-memory operations retire in order, and everything older has to have landed).
         floatx4 bias_q[TK];
 #pragma unroll
-        for (int tk = 0; tk < TK; ++tk) {
-            const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + c4 * 4;
-            bias_q[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if ((epi & 1) && ofm < a.Kb * 16) bias_q[tk] = *reinterpret_cast<const floatx4 *>(a.bias + ofm);
-        }
-        if (epi & 1)
+        for (int tk = 0; tk < TK; ++tk) bias_q[tk] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (epi & 1) {
+#pragma unroll
+            for (int tk = 0; tk < TK; ++tk) {
+                const int ofm = tc.ktile * KT + (wk * TK + tk) * 32 + c4 * 4;
+                if (ofm < a.Kb * 16) bias_q[tk] = *reinterpret_cast<const floatx4 *>(a.bias + ofm);
+            }
             wait_vm_and_barrier<TK>();
-        else
+        } else {
             wait_vm_and_barrier<0>();  // every wave has read its last fragments: the ring may be overwritten
+        }
         // Two instances of the loop: the plain one has no branch between the LDS reads and the stores of a tile, so
         // the four reads are issued together and the stores follow as the data return.
         auto store_tiles = [&](auto fused_tag) {
@@ -225,15 +227,21 @@ __device__ inline void write_out(const ConvArgs &a, const TileCoord &tc, floatx1
                     const int ofm0 = tc.ktile * KT + (wk * TK + tk) * 32;  // uniform; this lane: + c4 * 4
                     const bool kok = ofm0 + c4 * 4 < a.Kb * 16;            // K not a multiple of the tile: padded channels are dropped
                     const int soff = (ofm0 >> 4) * plane;
-                    const floatx4 bias = bias_q[tk];
-                    // all four reads first, so that the branches of the fused epilogue do not sit between a read and
-                    // its store (the reads' latency is then paid once per tile, not once per store)
+                    const floatx4 bias = bias_q[tk];  // (zero and unused in the plain instance)
+                    // fused: all four reads first, so that the branches on the epilogue flags do not sit between a read
+                    // and its store (the plain instance has no such branches and is left to the scheduler)
                     floatx4 vq[4];
+                    if constexpr (FUSED) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) vq[i] = *reinterpret_cast<const floatx4 *>(stage + (rp + 8 * i) * EPITCH + c4 * 4);
+                        for (int i = 0; i < 4; ++i) vq[i] = *reinterpret_cast<const floatx4 *>(stage + (rp + 8 * i) * EPITCH + c4 * 4);
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        floatx4 v = vq[i];
+                        floatx4 v;
+                        if constexpr (FUSED)
+                            v = vq[i];
+                        else
+                            v = *reinterpret_cast<const floatx4 *>(stage + (rp + 8 * i) * EPITCH + c4 * 4);
                         const unsigned voff = kok ? vpix[i] : kOobOffset;
                         if constexpr (FUSED) {
                             // bias, max(., 0), optional rounding to bf16
