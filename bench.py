@@ -121,6 +121,21 @@ class _GraphTimer:
         return e0.elapsed_time(e1) * 1e3 / (n * self.per_graph)
 
 
+def _launch_us(fn, precondition_ms: float, min_ms: float = 100.0):
+    """(microseconds per launch, how it was timed): graph replay, or, should capture fail on this runtime, an eager
+    loop (which reads high for launches shorter than a call through the binding)."""
+    import torch
+    try:
+        gt = _GraphTimer(fn)
+        _precondition(gt.replay, precondition_ms)
+        return gt.time_us(min_ms), "graph replay"
+    except Exception as e:   # never lose the bench line over the timing method
+        torch.cuda.synchronize()
+        _precondition(fn, precondition_ms)
+        _, ms = _time_steps(fn, 2000, 20)
+        return ms * 1e3, f"eager loop (graph capture failed: {type(e).__name__})"
+
+
 def _time_each(fn, launches: int):
     """Mean duration in ms of single launches, each bracketed by its own pair of HIP events on the launch
     stream.  The event records between launches keep consecutive launches from overlapping and add a few
@@ -164,24 +179,21 @@ def _layer_rows(ps, wl, torch, dtype_name: str, workspace, ws_cap: int):
         oi = torch.empty(ps.ps_blocked_out_bytes(dl) // 4, device=dev, dtype=torch.float32)
         t = ps.ps_tile_pick(dl, True, ws_cap)
         fn = lambda: ps.ps_conv2d_fwd_ws(dl, None, xi, wi, oi, workspace, ws_cap)   # the library picks (cached)
-        gt = _GraphTimer(fn)
-        _precondition(gt.replay, 60.0)
-        us = gt.time_us(100.0)
+        us, how = _launch_us(fn, 60.0)
         tf = L.flops / (us * 1e-6) * 1e-12
         t_roof = max(L.flops / (PEAK_TFLOPS[dtype_name] * 1e12), L.algorithmic_bytes(es) / (HBM_PEAK_GBS * 1e9))
         row = {"layer": L.name, "us": round(us, 2), "TFLOP/s": round(tf, 2),
                "frac_mfma_peak": round(tf / PEAK_TFLOPS[dtype_name], 4),
                "frac_min_mfma_hbm_roofline": round(t_roof / (us * 1e-6), 4),
                "tile": list(t.as_tuple()), "kernel": ps.KERNEL_NAMES[ps.ps_tile_kernel(dl, t)]}
+        if how != "graph replay":
+            row["timing"] = how
         # the paper's protocol with k = 3 (Section 4.2): the library runs its three best-ranked tiles and keeps the
         # fastest; the same call is then timed again (the figures above are k = 1, the paper's own setting)
         t3, _, _ = ps.ps_tile_autotune(dl, 3, xi, wi, oi, workspace, ws_cap)
         if t3.as_tuple() != t.as_tuple():
-            gt3 = _GraphTimer(fn)                # captured anew: the call now launches the tile the library kept
-            _precondition(gt3.replay, 20.0)
-            row["top3"] = {"tile": list(t3.as_tuple()), "us": round(gt3.time_us(100.0), 2)}
-            del gt3
-        del gt
+            us3, _ = _launch_us(fn, 20.0)        # captured anew: the call now launches the tile the library kept
+            row["top3"] = {"tile": list(t3.as_tuple()), "us": round(us3, 2)}
         rows.append(row)
         del xi, wi, oi
     n = len(base)
@@ -394,14 +406,12 @@ def main(argv=None) -> int:
         _, b_eager_ms = _time_steps(hb.step, max(a.steps, 1000), max(a.warmup, 100))
         # the launch takes about as long as one call through the Python binding costs the host: the figure of record is
         # the same launch replayed from a HIP graph (see _GraphTimer), the eager loop's is reported beside it
-        gtb = _GraphTimer(hb.step)
-        _precondition(gtb.replay, 40.0)
-        b_ms = gtb.time_us(100.0) * 1e-3
-        del gtb
+        b_us, b_how = _launch_us(hb.step, 40.0)
+        b_ms = b_us * 1e-3
         b_alg = wl.CFG2.algorithmic_bytes(2)
         b_tf = wl.CFG2.flops / (b_ms * 1e-3) * 1e-12
         bf16 = {"workload": "same layer, inputs and filters rounded to bf16 (nearest even), fp32 accumulate and output",
-                "us": round(b_ms * 1e3, 2), "timing": "launches replayed from a HIP graph", "eager_python_loop_us": round(b_eager_ms * 1e3, 2),
+                "us": round(b_ms * 1e3, 2), "timing": b_how, "eager_python_loop_us": round(b_eager_ms * 1e3, 2),
                 "TFLOP/s": round(b_tf, 1), "frac_mfma_peak": round(b_tf / PEAK_TFLOPS["bf16"], 4),
                 "roofline": {"bound": "hbm", "achieved": round(b_alg / (b_ms * 1e-3) * 1e-9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(b_alg / (b_ms * 1e-3) * 1e-9 / HBM_PEAK_GBS, 4),
@@ -419,10 +429,7 @@ def main(argv=None) -> int:
                 continue
             fn = (lambda H=H, out=out, odt=odt: ps.ps_conv2d_fwd_fused(H.d, None, H.xb, H.wb, out, workspace, WS_CAP,
                                                                        bias=bias, relu=True, out_dtype=odt))
-            gtf = _GraphTimer(fn)
-            _precondition(gtf.replay, 40.0)
-            fused[name] = round(gtf.time_us(100.0), 2)
-            del gtf
+            fused[name] = round(_launch_us(fn, 40.0)[0], 2)
         bf16["fused_epilogue"] = fused
         if not a.no_layers:
             bf16["layers"], bf16["layers_aggregate"] = _layer_rows(ps, wl, torch, "bf16", workspace, WS_CAP)
