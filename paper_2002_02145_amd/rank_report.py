@@ -1,4 +1,5 @@
-"""Ranking report over an exhaustive sweep (output of ``autotune --rows --out FILE``); runs on the host.
+"""Ranking report over an exhaustive sweep (output of ``autotune --rows --out FILE`` or a stored sweep of ``data/``); runs
+on the host.
 
 Two questions, both from Section 4.2 of the paper:
 
@@ -72,8 +73,9 @@ def report(path: str, dtype: str, with_paper_cost: bool = True, out=sys.stdout) 
         r = json.loads(line)
         L = named[r["layer"]]
         d = ps.ConvDesc.of(L, dt)
-        meas = {tuple(x["tile"]): x["us"] for x in r["rows"]}
-        use_ws = r.get("split_reduction") == "workspace"
+        # rows as autotune --rows writes them ({"tile": [...], "us": ...}) or in the compact stored form ([kt, mt, ring, split, order, us])
+        meas = {(tuple(x["tile"]) if isinstance(x, dict) else tuple(x[:5])): (x["us"] if isinstance(x, dict) else x[5]) for x in r["rows"]}
+        use_ws = r.get("split_reduction", "workspace") == "workspace"
         model = {t: (ps.ps_tile_cost_ws_us if use_ws else ps.ps_tile_cost_us)(d, ps.Tile(*t)) for t in meas}
         model = {t: c for t, c in model.items() if c > 0}
         best = min(meas.values())
@@ -109,7 +111,7 @@ def report(path: str, dtype: str, with_paper_cost: bool = True, out=sys.stdout) 
 
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("sweep", help="JSON-lines file written by autotune --rows --out")
+    ap.add_argument("sweep", help="JSON-lines file written by autotune --rows --out, or a stored sweep (data/sweep_*_N28.jsonl)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-paper-cost", action="store_true")
     a = ap.parse_args(argv)
