@@ -239,8 +239,9 @@ double model_cost(const Dims &dm, const ps_tile &t, const ShapeInfo &sh, bool wi
     } else if (f32) {
         // Workgroups that share a compute unit hide part of each other's set-up and stores.
         const double hidden = 1.0 + 0.5 * (std::min(occ, per_cu) - 1.0);
-        t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + c.fill_clk + per_cu * clk_wg / hidden +
-                  per_cu * (t.ring - 2) * 250.0) / c.clock_hz;  // a deeper ring takes longer to fill, per workgroup
+        // (a deeper ring takes longer to fill, per workgroup: 150 clk per extra slot, hidden like the rest of the set-up)
+        t_mfma = (per_simd * (clk_wave + clk_iter_overhead) + c.fill_clk +
+                  per_cu * (clk_wg + (t.ring - 2) * 150.0) / hidden) / c.clock_hz;
     } else {
         // 16-bit tiles are short enough that their set-up and stores mostly hide behind other workgroups; what
         // shows is the fill of every round of resident workgroups

@@ -35,7 +35,7 @@ def _losses(fname, dtype):
 @pytest.mark.parametrize("fname,dtype,worst,mean", [
     ("sweep_f32_N28.jsonl", ps.PS_F32, 0.10, 0.02),
     ("sweep_bf16_N28.jsonl", ps.PS_BF16, 0.13, 0.03),     # 1x1 256->1024 at 14x14: 8.6 against 7.7 us (12.4 %)
-    ("sweep_f32_N8.jsonl", ps.PS_F32, 0.10, 0.04),
+    ("sweep_f32_N8.jsonl", ps.PS_F32, 0.08, 0.03),
     # N = 1: 3x3 512 at 7x7 is a 16-way split whose baked loop no longer pads its two c-blocks (12.3 us); the model
     # still ranks a 12-way split on the general loop first (15.0 us, 22 %)
     ("sweep_f32_N1.jsonl", ps.PS_F32, 0.23, 0.04),
@@ -66,7 +66,7 @@ def test_pick_is_close_to_the_sweeps_best(fname, dtype, worst, mean):
     ("sweep_bf16_validation_N28.jsonl", ps.PS_BF16, 0.06, 0.015),
     # First layers of image networks (three input channels; tap-packed loops), nothing adjusted on them: fp32 15.1 % on
     # 11x11 into 96 channels (32-wide channel tiles, which need no padding, rank too well).
-    ("sweep_f32_first_N28.jsonl", ps.PS_F32, 0.16, 0.08),
+    ("sweep_f32_first_N28.jsonl", ps.PS_F32, 0.16, 0.065),
     ("sweep_bf16_first_N28.jsonl", ps.PS_BF16, 0.05, 0.01),
 ])
 def test_pick_on_layers_the_model_was_not_calibrated_on(fname, dtype, worst, mean):
